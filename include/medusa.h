@@ -1,0 +1,201 @@
+/*
+ * libmedusa_hip — static-tree Medusa verification for a pre-norm decoder on MI355X (gfx950).
+ *
+ * C ABI.  Every entry point only ENQUEUES work on the caller's HIP stream (passed as void*, NULL =
+ * the default stream): no call allocates device memory, synchronises, or copies to the host, so a
+ * decode loop can be chained without the host seeing any result (the point of the paper's Section
+ * 3.2 "Zero-Copy Retrieval Strategy").  Unless a parameter says HOST, every pointer is a DEVICE
+ * pointer owned by the caller and must stay valid until the stream reaches the enqueued work.
+ * Descriptor structs are HOST structs read during the call.
+ *
+ * Return value: mdz_status (0 = ok, negative = error).  On an error nothing has been enqueued and
+ * medusa_last_error() describes the failure.  No exceptions, no aborts.
+ *
+ * Storage dtype (mdz_model_desc.dtype): the element type of weights, embeddings, norm gains, the
+ * KV cache and the `hidden` tensors at the boundary: bf16 or fp32.  The residual stream and all
+ * logits are fp32 in both modes.  Token ids, lengths and indices are int32.
+ *
+ * Static trees (Section 3.2, "Tensorization of Tree Topology"): the candidate tree is fixed at
+ * compile time.  Node 0 is the root (the base model's own next token, depth 0); depth k holds
+ * candidates of Medusa head k (Section 3.1: head k predicts position t+k+1).  A node is a tuple of
+ * per-head candidate ranks; nodes are ordered by depth, then lexicographically.  For each tree the
+ * library holds: parent[T], depth[T], cand_slot[T] (index into the flat candidate buffer
+ * [root | top-k of head 1 | ... | top-k of head K]), anc_mask[T] (bit j of anc_mask[i] set iff node
+ * j is i or an ancestor of i: the paper's [T,T] visibility matrix, one 64-bit word per row) and
+ * retrieve[n_paths][K+1] (node indices root->leaf per leaf, leaves ascending, padded with -1: the
+ * paper's retrieve table).
+ */
+#ifndef MEDUSA_H
+#define MEDUSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MDZ_OK = 0,
+  MDZ_EINVAL = -1,       /* null pointer, negative size, bad enum */
+  MDZ_ESHAPE = -2,       /* sizes inconsistent with each other or with the tree */
+  MDZ_EUNSUPPORTED = -3, /* valid but not built (e.g. a head_dim the kernels do not cover) */
+  MDZ_EWORKSPACE = -4,   /* workspace smaller than medusa_workspace_bytes() */
+  MDZ_EHIP = -5          /* a HIP runtime call failed (message holds hipGetErrorString) */
+} mdz_status;
+
+typedef enum { MDZ_TREE_15 = 0, MDZ_TREE_64 = 1 } mdz_tree_id;
+typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1 } mdz_dtype;
+
+#define MDZ_MAX_HEADS 8
+
+/* HOST struct: the decoder's shape. d == n_heads * head_dim (multi-head attention, no bias). */
+typedef struct {
+  int32_t d, n_heads, head_dim, ffn, vocab, n_layers;
+  int32_t dtype; /* mdz_dtype */
+  int32_t tree;  /* mdz_tree_id: fixes T, K and the per-head top-k sizes */
+  float rms_eps;
+  float rope_base;
+} mdz_model_desc;
+
+/* HOST struct of device pointers: one decoder layer.  Matrices are in the library's PACKED layout
+ * (see medusa_pack_weight): wqkv = rows of Wq, Wk, Wv stacked ([3d, d]); wgateup = Wgate and Wup with
+ * their row tiles interleaved (tile 2j = gate tile j, tile 2j+1 = up tile j; [2*ffn, d]).
+ * g_attn, g_ffn: RMSNorm gains [d], storage dtype. */
+typedef struct {
+  const void* wqkv;
+  const void* wo;      /* [d, d] */
+  const void* wgateup; /* [2*ffn, d] */
+  const void* wdown;   /* [d, ffn] */
+  const void* g_attn;
+  const void* g_ffn;
+} mdz_layer_weights;
+
+/* HOST struct.  layers: HOST array of n_layers entries.  embed: [vocab, d] ROW-MAJOR storage dtype
+ * (it is gathered, not multiplied).  lm_head: packed [vocab, d].  Medusa head k (0-based here):
+ * head_w1[k] packed [d, d], head_b1[k] bias [d] storage dtype or NULL, head_lm[k] packed [vocab, d].
+ * head_b1 itself may be NULL (no head has a bias). */
+typedef struct {
+  const mdz_layer_weights* layers;
+  const void* embed;
+  const void* lm_head;
+  const void* g_final;
+  int32_t n_medusa;
+  const void* const* head_w1; /* HOST array [n_medusa] */
+  const void* const* head_b1; /* HOST array [n_medusa] or NULL */
+  const void* const* head_lm; /* HOST array [n_medusa] */
+} mdz_weights;
+
+/* HOST struct: the KV cache.  k and v are two device allocations of medusa_kv_bytes() bytes each whose
+ * internal layout belongs to the library (tiled for the attention kernels); fill and inspect them with
+ * medusa_kv_write / medusa_kv_read.  cap = slots per sequence; a verify pass with prefix length S
+ * writes slots S..S+T-1, so S + T <= cap is required. */
+typedef struct {
+  void* k;
+  void* v;
+  int32_t n_layers, batch, n_heads, head_dim, cap;
+  int32_t dtype; /* mdz_dtype */
+} mdz_kv_desc;
+
+/* ---- introspection (all HOST out-pointers) ------------------------------------------------- */
+
+/* Sizes of a compiled-in tree: T nodes, K heads, n_paths leaves, n_cand = 1 + sum of top-k sizes.
+ * topk (nullable) receives K entries (array of at least MDZ_MAX_HEADS ints). */
+int medusa_tree_info(int tree, int32_t* T, int32_t* K, int32_t* n_paths, int32_t* n_cand, int32_t* topk);
+
+/* Copies the compiled-in tables to HOST buffers (any may be NULL): parent[T], depth[T], cand_slot[T],
+ * anc_mask[T], retrieve[n_paths*(K+1)].  Lets a caller audit exactly what the kernels use. */
+int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_slot, uint64_t* anc_mask,
+                       int32_t* retrieve);
+
+/* Never NULL; thread-local; valid until the next failing call on this thread. */
+const char* medusa_last_error(void);
+
+/* ---- weight packing (one-time, outside any timed region) ------------------------------------ */
+
+/* Rows per packed tile for a dtype (32 for bf16, 16 for fp32). */
+int medusa_pack_tile_rows(int dtype);
+
+/* Bytes of a packed [n_rows, k] matrix (n_rows and k rounded up to the tile sizes; padding is zero). */
+int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
+
+/* Re-tiles a ROW-MAJOR [n_rows, k] matrix `src` (row r = output feature r, contiguous over input
+ * features: y = W x) into the streaming order of the GEMM kernels, same element type, same bytes.
+ * Source row tile j (rows j*R .. j*R+R-1, R = medusa_pack_tile_rows) lands at tile index
+ * tile_offset + j*tile_stride of `dst`, a packed matrix of dst_rows rows in total, so several matrices
+ * can be stacked (wqkv: offsets 0, d/R, 2d/R, stride 1) or interleaved (wgateup: offsets 0 and 1,
+ * stride 2).  n_rows must be a multiple of R unless tile_stride == 1 and this is the last matrix. */
+int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
+                       int64_t tile_offset, int64_t tile_stride, void* stream);
+
+/* ---- KV cache ------------------------------------------------------------------------------- */
+
+/* Bytes of EACH of desc->k and desc->v (negative = mdz_status). */
+int64_t medusa_kv_bytes(const mdz_kv_desc* desc);
+
+/* Copies n rows starting at slot pos0 of sequence `seq`, layer `layer`, between the cache and plain
+ * buffers k_rows / v_rows laid out [n_heads][n][head_dim] in the storage dtype.  write: buffers ->
+ * cache; read: cache -> buffers.  Requires 0 <= pos0, pos0 + n <= cap. */
+int medusa_kv_write(const mdz_kv_desc* desc, int layer, int seq, int pos0, int n, const void* k_rows,
+                    const void* v_rows, void* stream);
+int medusa_kv_read(const mdz_kv_desc* desc, int layer, int seq, int pos0, int n, void* k_rows, void* v_rows,
+                   void* stream);
+
+/* ---- workspace ------------------------------------------------------------------------------ */
+
+/* Bytes of scratch any of the calls below may need for batch B and prefix lengths <= max_prefix.
+ * The caller allocates it once; calls on different streams need different workspaces. */
+int64_t medusa_workspace_bytes(const mdz_model_desc* model, int B, int max_prefix);
+
+/* ---- the hot path --------------------------------------------------------------------------- */
+
+/* Section 3.1 (Medusa heads).  For each sequence b the input row is hidden[b][src_row[b]] (src_row NULL
+ * => row 0), the post-final-norm hidden state the base LM head reads.  Head k = 1..K:
+ * z = h + SiLU(W1_k h + b1_k); logits_k = Wlm_k z; candidates = the topk_k largest, descending,
+ * ties -> lower id.  The root candidate is root_token[b] if root_token != NULL, else the argmax of the
+ * base LM head on h.  Outputs: cand_flat [B, n_cand] = [root | head 1 | .. | head K]; tree_tokens [B, T]
+ * with tree_tokens[n] = cand_flat[cand_slot[n]]; head_logits_opt (nullable) [B, K+1, vocab] fp32
+ * (row 0 = base head, written only when it was computed).
+ * hidden: [B, Tsrc, d] storage dtype. */
+int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* hidden, const int32_t* src_row,
+                 const int32_t* root_token, int B, int Tsrc, int32_t* cand_flat, int32_t* tree_tokens,
+                 float* head_logits_opt, void* ws, int64_t ws_bytes, void* stream);
+
+/* Section 3.2 (single-pass tree verification), one decoder layer `layer` over x [B*T, d] fp32 (in/out,
+ * the residual stream).  For sequence b with prefix length S = seq_len[b] (clamped to [0, max_prefix]):
+ * RMSNorm -> q,k,v -> RoPE at position S + depth[n] (rotate-half pairing, angle pos*base^(-2i/hd)) ->
+ * k,v of node n stored to cache slot S + n -> node i attends to slots [0,S) and S+j for every j in
+ * anc_mask[i], scale 1/sqrt(head_dim) -> output projection + residual -> RMSNorm ->
+ * Wdown(SiLU(Wgate x) * Wup x) + residual.  seq_len: [B] device.  max_prefix + T <= kv->cap. */
+int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                      const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* ws,
+                      int64_t ws_bytes, void* stream);
+
+/* Section 3.2, the whole pass: embedding gather of tree_tokens [B, T] -> every layer as above -> final
+ * RMSNorm -> LM head -> per-node argmax (ties -> lowest id).  Outputs: node_argmax [B, T];
+ * hidden_out (nullable) [B, T, d] storage dtype = the post-final-norm hidden (what medusa_heads reads);
+ * logits_opt (nullable) [B, T, vocab] fp32. */
+int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const int32_t* tree_tokens,
+                     const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, int32_t* node_argmax,
+                     void* hidden_out, float* logits_opt, void* ws, int64_t ws_bytes, void* stream);
+
+/* Section 3.2 (zero-copy retrieval), greedy exact-match criterion.  Node n > 0 matches iff
+ * tree_tokens[n] == node_argmax[parent[n]]; the root always matches.  For every row of the retrieve
+ * table count the leading matching nodes; best_path = the longest (ties -> lowest row index),
+ * accept_len A in [1, K+1].  acc_nodes / acc_tokens [B, K+1] = first A nodes of that row and their
+ * tokens, -1 padded; last_node = acc_nodes[A-1]; next_root = node_argmax[last_node]. */
+int accept_longest_prefix(int tree, const int32_t* tree_tokens, const int32_t* node_argmax, int B,
+                          int32_t* accept_len, int32_t* best_path, int32_t* acc_nodes, int32_t* acc_tokens,
+                          int32_t* next_root, int32_t* last_node, void* stream);
+
+/* Section 3.2 (node -> KV position mapping).  For each sequence b with S = seq_len_inout[b] (clamped as
+ * above) and A = accept_len[b]: in every layer, for K and V, cache row S + j <- row S + acc_nodes[b][j]
+ * for j < A (in place, on the device, no staging buffer); kv_src_slots [B, K+1] = S + acc_nodes (-1
+ * padded); seq_len_inout[b] = S + A. */
+int kv_compact(const mdz_kv_desc* kv, int tree, const int32_t* acc_nodes, const int32_t* accept_len,
+               int32_t* seq_len_inout, int32_t* kv_src_slots, int B, int max_prefix, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEDUSA_H */

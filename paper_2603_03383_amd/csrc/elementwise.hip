@@ -1,0 +1,227 @@
+// Small row-wise kernels around the GEMMs: embedding gather, RMSNorm, RoPE + KV write, SwiGLU, the
+// Medusa head residual (Section 3.1: z = h + SiLU(W1 h)).
+#include "kernels.h"
+
+namespace mdz {
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// blockDim.x == 256
+__device__ inline float block_sum_256(float v, float* smem4) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) smem4[w] = v;
+  __syncthreads();
+  float r = smem4[0] + smem4[1] + smem4[2] + smem4[3];
+  __syncthreads();
+  return r;
+}
+
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restrict__ tokens, float* __restrict__ x,
+                             int d, int vocab) {
+  int r = blockIdx.x;
+  int tok = tokens[r];
+  tok = min(max(tok, 0), vocab - 1);
+  const T* src = embed + (int64_t)tok * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)r * d + i] = to_float(src[i]);
+}
+
+int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
+                 hipStream_t st) {
+  if (rows == 0) return MDZ_OK;
+  if (dtype == MDZ_BF16)
+    embed_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t*)embed, tokens, x, d, vocab);
+  else
+    embed_kernel<float><<<rows, 256, 0, st>>>((const float*)embed, tokens, x, d, vocab);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ g,
+                                                      T* __restrict__ xn, int d, float eps) {
+  __shared__ float red[4];
+  int r = blockIdx.x;
+  const float* xr = x + (int64_t)r * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) ss += xr[i] * xr[i];
+  ss = block_sum_256(ss, red);
+  float rs = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
+}
+
+int launch_rmsnorm(int dtype, const float* x, const void* g, void* xn, int rows, int d, float eps, hipStream_t st) {
+  if (rows == 0) return MDZ_OK;
+  if (dtype == MDZ_BF16)
+    rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, (const bf16_t*)g, (bf16_t*)xn, d, eps);
+  else
+    rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, (const float*)g, (float*)xn, d, eps);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+// One thread per (row, i): angle evaluated in double so that long prefixes keep full fp32 accuracy.
+__global__ void rope_table_kernel(int tree, const int32_t* __restrict__ seq_len, int B, int max_prefix, int half,
+                                  double log2_base, float* __restrict__ cs) {
+  const TreeTables& t = c_trees[tree];
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= B * t.T * half) return;
+  int i = idx % half;
+  int n = (idx / half) % t.T;
+  int b = idx / (half * t.T);
+  int S = min(max(seq_len[b], 0), max_prefix);
+  double pos = (double)(S + t.depth[n]);
+  double ang = pos * exp2(-(double)i / (double)half * log2_base);
+  cs[2 * idx] = (float)cos(ang);
+  cs[2 * idx + 1] = (float)sin(ang);
+}
+
+int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
+                      float* cs, hipStream_t st) {
+  const TreeTables* t = host_tree(tree);
+  int half = head_dim / 2;
+  int total = B * t->T * half;
+  if (total == 0) return MDZ_OK;
+  rope_table_kernel<<<(total + 255) / 256, 256, 0, st>>>(tree, seq_len, B, max_prefix, half,
+                                                         log2((double)rope_base), cs);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+// grid (B*T, n_heads), block = head_dim/2 threads... generalised: threads stride over i < half.
+template <typename T>
+__global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, const float* __restrict__ cs,
+                                    T* __restrict__ q_out, KvGeom g, T* __restrict__ kc, T* __restrict__ vc, int layer,
+                                    const int32_t* __restrict__ seq_len, int max_prefix) {
+  const TreeTables& t = c_trees[tree];
+  int row = blockIdx.x;  // b*T + n
+  int h = blockIdx.y;
+  int b = row / t.T, n = row % t.T;
+  int hd = g.head_dim, half = hd / 2, d = g.n_heads * hd;
+  int S = min(max(seq_len[b], 0), max_prefix);
+  int slot = S + n;
+  const float* qr = qkv + (int64_t)row * 3 * d + h * hd;
+  const float* kr = qr + d;
+  const float* vr = qr + 2 * d;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    float c = cs[((int64_t)row * half + i) * 2], s = cs[((int64_t)row * half + i) * 2 + 1];
+    float qa = qr[i], qb = qr[i + half];
+    float ka = kr[i], kb = kr[i + half];
+    q_out[(int64_t)row * d + h * hd + i] = from_float<T>(qa * c - qb * s);
+    q_out[(int64_t)row * d + h * hd + i + half] = from_float<T>(qb * c + qa * s);
+    kc[k_index(g, layer, b, h, slot, i)] = from_float<T>(ka * c - kb * s);
+    kc[k_index(g, layer, b, h, slot, i + half)] = from_float<T>(kb * c + ka * s);
+    vc[v_index(g, layer, b, h, slot, i)] = from_float<T>(vr[i]);
+    vc[v_index(g, layer, b, h, slot, i + half)] = from_float<T>(vr[i + half]);
+  }
+}
+
+int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, void* q_out, const KvGeom& g,
+                        void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
+                        hipStream_t st) {
+  const TreeTables* t = host_tree(tree);
+  if (B == 0) return MDZ_OK;
+  dim3 grid(B * t->T, g.n_heads);
+  int threads = g.head_dim / 2 <= 64 ? 64 : 128;
+  if (dtype == MDZ_BF16)
+    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
+                                                          layer, seq_len, max_prefix);
+  else
+    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv, cs, (float*)q_out, g, (float*)kc, (float*)vc,
+                                                         layer, seq_len, max_prefix);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+__device__ inline float silu_f(float v) { return v / (1.0f + expf(-v)); }
+
+// gate feature f sits at column (2*(f/R))*R + f%R of gu, up at (2*(f/R)+1)*R + f%R (R = tile rows)
+template <typename T>
+__global__ void swiglu_kernel(const float* __restrict__ gu, T* __restrict__ u, int M, int F) {
+  constexpr int R = Packed<T>::kTileRows;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)M * F) return;
+  int f = idx % F;
+  int64_t m = idx / F;
+  int64_t col = (int64_t)(2 * (f / R)) * R + f % R;
+  float gv = gu[m * 2 * F + col], uv = gu[m * 2 * F + col + R];
+  u[idx] = from_float<T>(silu_f(gv) * uv);
+}
+
+int launch_swiglu(int dtype, const float* gu, void* u, int M, int F, hipStream_t st) {
+  int64_t total = (int64_t)M * F;
+  if (total == 0) return MDZ_OK;
+  unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == MDZ_BF16)
+    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);
+  else
+    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu, (float*)u, M, F);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+template <typename T>
+__global__ void gather_rows_kernel(const T* __restrict__ hidden, const int32_t* __restrict__ src_row, int Tsrc, int d,
+                                   T* __restrict__ h) {
+  int b = blockIdx.x;
+  int r = src_row ? min(max(src_row[b], 0), Tsrc - 1) : 0;
+  const T* src = hidden + ((int64_t)b * Tsrc + r) * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(int64_t)b * d + i] = src[i];
+}
+
+int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, int B, int Tsrc, int d, void* h,
+                       hipStream_t st) {
+  if (B == 0) return MDZ_OK;
+  if (dtype == MDZ_BF16)
+    gather_rows_kernel<bf16_t><<<B, 256, 0, st>>>((const bf16_t*)hidden, src_row, Tsrc, d, (bf16_t*)h);
+  else
+    gather_rows_kernel<float><<<B, 256, 0, st>>>((const float*)hidden, src_row, Tsrc, d, (float*)h);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+template <typename T>
+__global__ void head_residual_kernel(const T* __restrict__ h, const float* __restrict__ pre, const T* __restrict__ b1,
+                                     T* __restrict__ z, int64_t n, int d) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  float p = pre[idx] + (b1 ? to_float(b1[idx % d]) : 0.f);
+  z[idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
+}
+
+int launch_head_residual(int dtype, const void* h, const float* pre, const void* b1, void* z, int B, int d,
+                         hipStream_t st) {
+  int64_t n = (int64_t)B * d;
+  if (n == 0) return MDZ_OK;
+  unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dtype == MDZ_BF16)
+    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre, (const bf16_t*)b1, (bf16_t*)z, n, d);
+  else
+    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre, (const float*)b1, (float*)z, n, d);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+template <typename T>
+__global__ void store_rows_kernel(const float* __restrict__ src, T* __restrict__ dst, int64_t n) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) dst[idx] = from_float<T>(src[idx]);
+}
+
+int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st) {
+  if (n == 0) return MDZ_OK;
+  unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dtype == MDZ_BF16)
+    store_rows_kernel<bf16_t><<<blocks, 256, 0, st>>>(src, (bf16_t*)dst, n);
+  else
+    store_rows_kernel<float><<<blocks, 256, 0, st>>>(src, (float*)dst, n);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+}  // namespace mdz

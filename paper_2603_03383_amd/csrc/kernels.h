@@ -1,0 +1,65 @@
+// Internal launch interface between the C-ABI layer (medusa_api.hip) and the kernel files.
+// Every function enqueues on `st` and returns an mdz_status.  All pointers are device pointers.
+#pragma once
+#include "common.h"
+
+namespace mdz {
+
+// ---- layout movers (layout.hip) ------------------------------------------------------------------
+int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
+                       int64_t tile_offset, int64_t tile_stride, hipStream_t st);
+int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n,
+                   void* k_rows, void* v_rows, bool to_cache, hipStream_t st);
+int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, const int32_t* acc_nodes,
+                      const int32_t* accept_len, int32_t* seq_len, int32_t* kv_src_slots, int B,
+                      int max_prefix, hipStream_t st);
+
+// ---- elementwise / small kernels (elementwise.hip) -------------------------------------------------
+int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
+                 hipStream_t st);
+// xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g, rounded to the storage dtype
+int launch_rmsnorm(int dtype, const float* x, const void* g, void* xn, int rows, int d, float eps,
+                   hipStream_t st);
+// cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32
+int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
+                      float* cs, hipStream_t st);
+// rotates q and k of qkv [B*T][3d] fp32; q -> q_out [B*T][d] storage dtype; k,v -> cache slots S_b + n
+int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, void* q_out, const KvGeom& g,
+                        void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
+                        hipStream_t st);
+// u[m][f] = SiLU(gate) * up from the tile-interleaved gate/up GEMM output gu [M][2F] fp32
+int launch_swiglu(int dtype, const float* gu, void* u, int M, int F, hipStream_t st);
+// gathers row src_row[b] of hidden [B][Tsrc][d] into h [B][d] (same dtype)
+int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, int B, int Tsrc, int d, void* h,
+                       hipStream_t st);
+// z = h + SiLU(pre + b1) -> storage dtype
+int launch_head_residual(int dtype, const void* h, const float* pre, const void* b1, void* z, int B, int d,
+                         hipStream_t st);
+// storage-dtype copy of fp32 rows (hidden_out)
+int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
+
+// ---- selection kernels (select.hip) -----------------------------------------------------------------
+// out[r] = argmax_v logits[r][v], ties -> lowest v
+int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, hipStream_t st);
+// out[r][0..k) = indices of the k largest of logits[r][:], descending, ties -> lower index
+int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld,
+                hipStream_t st);
+// dst[i * dst_stride] = src[i]
+int launch_scatter_i32(const int32_t* src, int32_t* dst, int n, int64_t dst_stride, hipStream_t st);
+int launch_tree_tokens(int tree, const int32_t* cand_flat, int32_t* tree_tokens, int B, hipStream_t st);
+int launch_accept(int tree, const int32_t* tree_tokens, const int32_t* node_argmax, int B, int32_t* accept_len,
+                  int32_t* best_path, int32_t* acc_nodes, int32_t* acc_tokens, int32_t* next_root,
+                  int32_t* last_node, hipStream_t st);
+
+// ---- GEMM: Y[m][n] (+)= sum_k X[m][k] * W[n][k], W packed, X storage dtype [M][K], Y fp32 ---------
+int launch_gemm(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy,
+                bool accumulate, hipStream_t st);
+
+// ---- tree-masked attention --------------------------------------------------------------------------
+// q [B*T][d] storage dtype (rotated); att_out [B*T][d] storage dtype
+int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
+                          int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                          int64_t scratch_bytes, hipStream_t st);
+int64_t tree_attention_scratch_bytes(int dtype, int tree, const KvGeom& g, int B, int max_prefix);
+
+}  // namespace mdz

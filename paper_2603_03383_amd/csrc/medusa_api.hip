@@ -1,0 +1,373 @@
+// C-ABI layer of libmedusa_hip: argument checking, workspace carving and the order of kernel launches.
+// Every step of the path runs in the kernels; this file only sequences them on the caller's stream.
+#include <stdarg.h>
+#include <string.h>
+
+#include "kernels.h"
+
+namespace mdz {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int launch_gemm_generic(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy,
+                        bool accumulate, hipStream_t st);
+int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
+                             int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                             hipStream_t st);
+
+int launch_gemm(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy, bool accumulate,
+                hipStream_t st) {
+  return launch_gemm_generic(dtype, X, Wp, Y, M, N, K, ldy, accumulate, st);
+}
+
+int64_t tree_attention_scratch_bytes(int, int, const KvGeom&, int, int) { return 0; }
+
+int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
+                          int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void*, int64_t,
+                          hipStream_t st) {
+  return launch_attention_generic(dtype, tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, st);
+}
+
+// ---- workspace ------------------------------------------------------------------------------------
+struct Workspace {
+  int64_t rope_cs, x, xn, qkv, q, att, gu, u, logits, h, pre, z, hlogits, attn_scratch, total;
+};
+
+static int64_t align256(int64_t v) { return (v + 255) & ~int64_t(255); }
+
+static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
+  const TreeTables* t = host_tree(m.tree);
+  const int64_t es = elem_bytes(m.dtype);
+  const int64_t rows = (int64_t)B * t->T;
+  Workspace w{};
+  int64_t off = 0;
+  auto take = [&](int64_t bytes) {
+    int64_t o = off;
+    off = align256(off + bytes);
+    return o;
+  };
+  w.rope_cs = take(rows * (m.head_dim / 2) * 2 * 4);
+  w.x = take(rows * m.d * 4);
+  w.xn = take(rows * m.d * es);
+  w.qkv = take(rows * 3 * m.d * 4);
+  w.q = take(rows * m.d * es);
+  w.att = take(rows * m.d * es);
+  w.gu = take(rows * 2 * m.ffn * 4);
+  w.u = take(rows * m.ffn * es);
+  w.logits = take(rows * (int64_t)m.vocab * 4);
+  w.h = take((int64_t)B * m.d * es);
+  w.pre = take((int64_t)B * m.d * 4);
+  w.z = take((int64_t)B * m.d * es);
+  w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
+  KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T};
+  w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
+  w.total = off;
+  return w;
+}
+
+static int check_model(const mdz_model_desc* m) {
+  MDZ_REQUIRE(m != nullptr, MDZ_EINVAL, "model descriptor is NULL");
+  MDZ_REQUIRE(m->dtype == MDZ_BF16 || m->dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", m->dtype);
+  MDZ_REQUIRE(host_tree(m->tree) != nullptr, MDZ_EINVAL, "bad tree id %d", m->tree);
+  MDZ_REQUIRE(m->d > 0 && m->n_heads > 0 && m->head_dim > 0 && m->ffn > 0 && m->vocab > 0 && m->n_layers > 0,
+              MDZ_EINVAL, "model sizes must be positive");
+  MDZ_REQUIRE(m->d == m->n_heads * m->head_dim, MDZ_ESHAPE, "d %d != n_heads %d * head_dim %d", m->d, m->n_heads,
+              m->head_dim);
+  MDZ_REQUIRE(m->head_dim % 2 == 0, MDZ_ESHAPE, "head_dim %d must be even (rotary pairs)", m->head_dim);
+  const int R = m->dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
+  MDZ_REQUIRE(m->ffn % R == 0 && m->d % R == 0, MDZ_ESHAPE, "d %d and ffn %d must be multiples of the tile height %d",
+              m->d, m->ffn, R);
+  MDZ_REQUIRE(m->dtype != MDZ_BF16 || (m->d % kKStepBf16 == 0 && m->ffn % kKStepBf16 == 0), MDZ_ESHAPE,
+              "bf16: d and ffn must be multiples of %d", kKStepBf16);
+  MDZ_REQUIRE(m->rms_eps >= 0.f && m->rope_base > 1.f, MDZ_EINVAL, "bad rms_eps / rope_base");
+  return MDZ_OK;
+}
+
+static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int max_prefix) {
+  MDZ_REQUIRE(kv != nullptr && kv->k != nullptr && kv->v != nullptr, MDZ_EINVAL, "kv descriptor or its buffers NULL");
+  MDZ_REQUIRE(kv->dtype == MDZ_BF16 || kv->dtype == MDZ_FP32, MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
+  MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
+              "kv sizes must be positive");
+  if (m) {
+    MDZ_REQUIRE(kv->dtype == m->dtype && kv->n_heads == m->n_heads && kv->head_dim == m->head_dim &&
+                    kv->n_layers >= m->n_layers,
+                MDZ_ESHAPE, "kv cache (L%d H%d hd%d dtype%d) does not match the model (L%d H%d hd%d dtype%d)",
+                kv->n_layers, kv->n_heads, kv->head_dim, kv->dtype, m->n_layers, m->n_heads, m->head_dim, m->dtype);
+  }
+  MDZ_REQUIRE(B >= 0 && B <= kv->batch, MDZ_ESHAPE, "B %d exceeds kv batch %d", B, kv->batch);
+  MDZ_REQUIRE(max_prefix >= 0, MDZ_EINVAL, "max_prefix %d < 0", max_prefix);
+  return MDZ_OK;
+}
+
+static KvGeom geom(const mdz_kv_desc* kv) { return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap}; }
+
+// One decoder layer over rows = B*T rows of x.
+static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int layer, float* x, const mdz_kv_desc* kv,
+                     const int32_t* seq_len, int B, int max_prefix, char* ws, const Workspace& w, hipStream_t st) {
+  const TreeTables* t = host_tree(m.tree);
+  const int rows = B * t->T;
+  const KvGeom g = geom(kv);
+  int rc;
+  float* cs = (float*)(ws + w.rope_cs);
+  void* xn = ws + w.xn;
+  float* qkv = (float*)(ws + w.qkv);
+  void* q = ws + w.q;
+  void* att = ws + w.att;
+  float* gu = (float*)(ws + w.gu);
+  void* u = ws + w.u;
+  if ((rc = launch_rmsnorm(m.dtype, x, lw.g_attn, xn, rows, m.d, m.rms_eps, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, qkv, rows, 3 * m.d, m.d, 3 * m.d, false, st))) return rc;
+  if ((rc = launch_rope_kvwrite(m.dtype, m.tree, qkv, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, st)))
+    return rc;
+  if ((rc = launch_tree_attention(m.dtype, m.tree, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
+                                  ws + w.attn_scratch, w.total - w.attn_scratch, st)))
+    return rc;
+  if ((rc = launch_gemm(m.dtype, att, lw.wo, x, rows, m.d, m.d, m.d, true, st))) return rc;
+  if ((rc = launch_rmsnorm(m.dtype, x, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, gu, rows, 2 * m.ffn, m.d, 2 * m.ffn, false, st))) return rc;
+  if ((rc = launch_swiglu(m.dtype, gu, u, rows, m.ffn, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, u, lw.wdown, x, rows, m.d, m.ffn, m.d, true, st))) return rc;
+  return MDZ_OK;
+}
+
+static int check_layer_weights(const mdz_layer_weights* lw) {
+  MDZ_REQUIRE(lw && lw->wqkv && lw->wo && lw->wgateup && lw->wdown && lw->g_attn && lw->g_ffn, MDZ_EINVAL,
+              "layer weights: NULL pointer");
+  return MDZ_OK;
+}
+
+}  // namespace mdz
+
+using namespace mdz;
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* medusa_last_error(void) { return g_err; }
+
+int medusa_tree_info(int tree, int32_t* T, int32_t* K, int32_t* n_paths, int32_t* n_cand, int32_t* topk) {
+  const TreeTables* t = host_tree(tree);
+  MDZ_REQUIRE(t != nullptr, MDZ_EINVAL, "bad tree id %d", tree);
+  if (T) *T = t->T;
+  if (K) *K = t->K;
+  if (n_paths) *n_paths = t->n_paths;
+  if (n_cand) *n_cand = t->n_cand;
+  if (topk)
+    for (int k = 0; k < t->K; ++k) topk[k] = t->caps[k];
+  return MDZ_OK;
+}
+
+int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_slot, uint64_t* anc_mask,
+                       int32_t* retrieve) {
+  const TreeTables* t = host_tree(tree);
+  MDZ_REQUIRE(t != nullptr, MDZ_EINVAL, "bad tree id %d", tree);
+  for (int n = 0; n < t->T; ++n) {
+    if (parent) parent[n] = t->parent[n];
+    if (depth) depth[n] = t->depth[n];
+    if (cand_slot) cand_slot[n] = t->cand_slot[n];
+    if (anc_mask) anc_mask[n] = t->anc_mask[n];
+  }
+  if (retrieve)
+    for (int p = 0; p < t->n_paths; ++p)
+      for (int c = 0; c <= t->K; ++c) retrieve[p * (t->K + 1) + c] = t->retrieve[p][c];
+  return MDZ_OK;
+}
+
+int medusa_pack_tile_rows(int dtype) {
+  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
+  return dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
+}
+
+int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k) {
+  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
+  MDZ_REQUIRE(n_rows > 0 && k > 0, MDZ_EINVAL, "packed_bytes: sizes must be positive");
+  if (dtype == MDZ_BF16) return round_up(n_rows, kTileRowsBf16) * Packed<bf16_t>::padded_k(k) * 2;
+  return round_up(n_rows, kTileRowsF32) * k * 4;
+}
+
+int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
+                       int64_t tile_offset, int64_t tile_stride, void* stream) {
+  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
+  MDZ_REQUIRE(src && dst, MDZ_EINVAL, "pack: NULL pointer");
+  MDZ_REQUIRE(n_rows > 0 && k > 0 && dst_rows >= n_rows, MDZ_EINVAL, "pack: bad sizes");
+  return launch_pack_weight(dtype, src, n_rows, k, dst, dst_rows, tile_offset, tile_stride, (hipStream_t)stream);
+}
+
+int64_t medusa_kv_bytes(const mdz_kv_desc* kv) {
+  MDZ_REQUIRE(kv != nullptr, MDZ_EINVAL, "kv descriptor NULL");
+  MDZ_REQUIRE(kv->dtype == MDZ_BF16 || kv->dtype == MDZ_FP32, MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
+  MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
+              "kv sizes must be positive");
+  return kv_elems(geom(kv)) * elem_bytes(kv->dtype);
+}
+
+static int kv_rw(const mdz_kv_desc* kv, int layer, int seq, int pos0, int n, void* k_rows, void* v_rows, bool to_cache,
+                 void* stream) {
+  int rc = check_kv(nullptr, kv, 0, 0);
+  if (rc) return rc;
+  MDZ_REQUIRE(layer >= 0 && layer < kv->n_layers && seq >= 0 && seq < kv->batch, MDZ_EINVAL,
+              "kv copy: layer %d / seq %d out of range", layer, seq);
+  MDZ_REQUIRE(pos0 >= 0 && n >= 0 && pos0 + n <= kv->cap, MDZ_ESHAPE, "kv copy: rows [%d,%d) exceed cap %d", pos0,
+              pos0 + n, kv->cap);
+  MDZ_REQUIRE(k_rows || v_rows, MDZ_EINVAL, "kv copy: both row buffers NULL");
+  return launch_kv_copy(kv->dtype, geom(kv), kv->k, kv->v, layer, seq, pos0, n, k_rows, v_rows, to_cache,
+                        (hipStream_t)stream);
+}
+
+int medusa_kv_write(const mdz_kv_desc* kv, int layer, int seq, int pos0, int n, const void* k_rows, const void* v_rows,
+                    void* stream) {
+  return kv_rw(kv, layer, seq, pos0, n, (void*)k_rows, (void*)v_rows, true, stream);
+}
+
+int medusa_kv_read(const mdz_kv_desc* kv, int layer, int seq, int pos0, int n, void* k_rows, void* v_rows,
+                   void* stream) {
+  return kv_rw(kv, layer, seq, pos0, n, k_rows, v_rows, false, stream);
+}
+
+int64_t medusa_workspace_bytes(const mdz_model_desc* model, int B, int max_prefix) {
+  int rc = check_model(model);
+  if (rc) return rc;
+  MDZ_REQUIRE(B >= 0 && max_prefix >= 0, MDZ_EINVAL, "workspace: negative B or max_prefix");
+  return carve(*model, B, max_prefix).total;
+}
+
+int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* hidden, const int32_t* src_row,
+                 const int32_t* root_token, int B, int Tsrc, int32_t* cand_flat, int32_t* tree_tokens,
+                 float* head_logits_opt, void* ws, int64_t ws_bytes, void* stream) {
+  int rc = check_model(model);
+  if (rc) return rc;
+  const mdz_model_desc& m = *model;
+  const TreeTables* t = host_tree(m.tree);
+  MDZ_REQUIRE(w && hidden && cand_flat && tree_tokens && ws, MDZ_EINVAL, "medusa_heads: NULL pointer");
+  MDZ_REQUIRE(B >= 0 && Tsrc >= 1, MDZ_EINVAL, "medusa_heads: B %d, Tsrc %d", B, Tsrc);
+  MDZ_REQUIRE(w->n_medusa == t->K, MDZ_ESHAPE, "medusa_heads: %d heads given, the tree has depth %d", w->n_medusa,
+              t->K);
+  MDZ_REQUIRE(w->head_w1 && w->head_lm, MDZ_EINVAL, "medusa_heads: head weight arrays NULL");
+  for (int k = 0; k < t->K; ++k)
+    MDZ_REQUIRE(w->head_w1[k] && w->head_lm[k], MDZ_EINVAL, "medusa_heads: head %d weights NULL", k);
+  MDZ_REQUIRE(root_token || w->lm_head, MDZ_EINVAL, "medusa_heads: need root_token or the base lm_head");
+  const Workspace L = carve(m, B, 0);
+  MDZ_REQUIRE(ws_bytes >= L.total, MDZ_EWORKSPACE, "medusa_heads: workspace %lld < %lld bytes", (long long)ws_bytes,
+              (long long)L.total);
+  if (B == 0) return MDZ_OK;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = (char*)ws;
+  void* h = wsb + L.h;
+  float* pre = (float*)(wsb + L.pre);
+  void* z = wsb + L.z;
+  const int64_t V = m.vocab;
+  const int64_t ld = (int64_t)(t->K + 1) * V;  // row stride of the [B][K+1][V] logits
+  float* hl = head_logits_opt ? head_logits_opt : (float*)(wsb + L.hlogits);
+  if ((rc = launch_gather_rows(m.dtype, hidden, src_row, B, Tsrc, m.d, h, st))) return rc;
+  // slot 0: root token
+  if (root_token) {
+    if ((rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
+  } else {
+    if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, false, st))) return rc;
+    if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, st))) return rc;
+  }
+  int seg = 1;
+  for (int k = 0; k < t->K; ++k) {
+    const void* b1 = w->head_b1 ? w->head_b1[k] : nullptr;
+    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], pre, B, m.d, m.d, m.d, false, st))) return rc;
+    if ((rc = launch_head_residual(m.dtype, h, pre, b1, z, B, m.d, st))) return rc;
+    float* lk = hl + (int64_t)(k + 1) * V;
+    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, false, st))) return rc;
+    if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, st))) return rc;
+    seg += t->caps[k];
+  }
+  return launch_tree_tokens(m.tree, cand_flat, tree_tokens, B, st);
+}
+
+int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                      const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* ws, int64_t ws_bytes,
+                      void* stream) {
+  int rc = check_model(model);
+  if (rc) return rc;
+  if ((rc = check_layer_weights(lw))) return rc;
+  if ((rc = check_kv(model, kv, B, max_prefix))) return rc;
+  const TreeTables* t = host_tree(model->tree);
+  MDZ_REQUIRE(x_inout && seq_len && ws, MDZ_EINVAL, "tree_verify_layer: NULL pointer");
+  MDZ_REQUIRE(layer >= 0 && layer < kv->n_layers, MDZ_EINVAL, "tree_verify_layer: layer %d outside the cache's %d",
+              layer, kv->n_layers);
+  MDZ_REQUIRE(max_prefix + t->T <= kv->cap, MDZ_ESHAPE, "max_prefix %d + T %d exceeds kv cap %d", max_prefix, t->T,
+              kv->cap);
+  const Workspace L = carve(*model, B, max_prefix);
+  MDZ_REQUIRE(ws_bytes >= L.total, MDZ_EWORKSPACE, "tree_verify_layer: workspace %lld < %lld bytes",
+              (long long)ws_bytes, (long long)L.total);
+  if (B == 0) return MDZ_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = launch_rope_table(model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
+                              (float*)((char*)ws + L.rope_cs), st)))
+    return rc;
+  return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, st);
+}
+
+int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const int32_t* tree_tokens,
+                     const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, int32_t* node_argmax,
+                     void* hidden_out, float* logits_opt, void* ws, int64_t ws_bytes, void* stream) {
+  int rc = check_model(model);
+  if (rc) return rc;
+  const mdz_model_desc& m = *model;
+  MDZ_REQUIRE(w && w->layers && w->embed && w->lm_head && w->g_final, MDZ_EINVAL, "tree_verify_step: NULL weights");
+  for (int l = 0; l < m.n_layers; ++l)
+    if ((rc = check_layer_weights(&w->layers[l]))) return rc;
+  if ((rc = check_kv(model, kv, B, max_prefix))) return rc;
+  const TreeTables* t = host_tree(m.tree);
+  MDZ_REQUIRE(tree_tokens && seq_len && node_argmax && ws, MDZ_EINVAL, "tree_verify_step: NULL pointer");
+  MDZ_REQUIRE(max_prefix + t->T <= kv->cap, MDZ_ESHAPE, "max_prefix %d + T %d exceeds kv cap %d", max_prefix, t->T,
+              kv->cap);
+  const Workspace L = carve(m, B, max_prefix);
+  MDZ_REQUIRE(ws_bytes >= L.total, MDZ_EWORKSPACE, "tree_verify_step: workspace %lld < %lld bytes",
+              (long long)ws_bytes, (long long)L.total);
+  if (B == 0) return MDZ_OK;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = (char*)ws;
+  const int rows = B * t->T;
+  float* x = (float*)(wsb + L.x);
+  if ((rc = launch_rope_table(m.tree, seq_len, B, max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs), st)))
+    return rc;
+  if ((rc = launch_embed(m.dtype, w->embed, tree_tokens, x, rows, m.d, m.vocab, st))) return rc;
+  for (int l = 0; l < m.n_layers; ++l)
+    if ((rc = run_layer(m, w->layers[l], l, x, kv, seq_len, B, max_prefix, wsb, L, st))) return rc;
+  void* hid = hidden_out ? hidden_out : (void*)(wsb + L.xn);
+  if ((rc = launch_rmsnorm(m.dtype, x, w->g_final, hid, rows, m.d, m.rms_eps, st))) return rc;
+  float* logits = logits_opt ? logits_opt : (float*)(wsb + L.logits);
+  if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, false, st))) return rc;
+  return launch_argmax(logits, rows, m.vocab, m.vocab, node_argmax, st);
+}
+
+int accept_longest_prefix(int tree, const int32_t* tree_tokens, const int32_t* node_argmax, int B,
+                          int32_t* accept_len, int32_t* best_path, int32_t* acc_nodes, int32_t* acc_tokens,
+                          int32_t* next_root, int32_t* last_node, void* stream) {
+  MDZ_REQUIRE(host_tree(tree) != nullptr, MDZ_EINVAL, "bad tree id %d", tree);
+  MDZ_REQUIRE(B >= 0, MDZ_EINVAL, "accept: B %d < 0", B);
+  MDZ_REQUIRE(tree_tokens && node_argmax && accept_len && best_path && acc_nodes && acc_tokens && next_root &&
+                  last_node,
+              MDZ_EINVAL, "accept_longest_prefix: NULL pointer");
+  return launch_accept(tree, tree_tokens, node_argmax, B, accept_len, best_path, acc_nodes, acc_tokens, next_root,
+                       last_node, (hipStream_t)stream);
+}
+
+int kv_compact(const mdz_kv_desc* kv, int tree, const int32_t* acc_nodes, const int32_t* accept_len,
+               int32_t* seq_len_inout, int32_t* kv_src_slots, int B, int max_prefix, void* stream) {
+  const TreeTables* t = host_tree(tree);
+  MDZ_REQUIRE(t != nullptr, MDZ_EINVAL, "bad tree id %d", tree);
+  int rc = check_kv(nullptr, kv, B, max_prefix);
+  if (rc) return rc;
+  MDZ_REQUIRE(acc_nodes && accept_len && seq_len_inout && kv_src_slots, MDZ_EINVAL, "kv_compact: NULL pointer");
+  MDZ_REQUIRE(max_prefix + t->T <= kv->cap, MDZ_ESHAPE, "max_prefix %d + T %d exceeds kv cap %d", max_prefix, t->T,
+              kv->cap);
+  return launch_kv_compact(kv->dtype, geom(kv), kv->k, kv->v, tree, acc_nodes, accept_len, seq_len_inout, kv_src_slots,
+                           B, max_prefix, (hipStream_t)stream);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

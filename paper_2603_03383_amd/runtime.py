@@ -1,0 +1,183 @@
+"""Holders for device memory around the C-ABI calls: packed model weights, KV cache, per-step buffers.
+
+No arithmetic of the method lives here: tensors are allocated with torch, handed to the library's pack /
+KV-write kernels, and their pointers are stored in the ctypes structs the entry points take.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype: int):
+    return torch.bfloat16 if dtype == B.MDZ_BF16 else torch.float32
+
+
+class DeviceModel:
+    """Packed weights of one decoder (+ Medusa heads) on one GPU."""
+
+    def __init__(self, *, d, n_heads, head_dim, ffn, vocab, n_layers, dtype: str, tree: str, rms_eps=1e-5,
+                 rope_base=10000.0, device="cuda:0"):
+        self.desc = B.ModelDesc(d, n_heads, head_dim, ffn, vocab, n_layers, B.DTYPES[dtype], B.TREES[tree], rms_eps,
+                                rope_base)
+        self.device = torch.device(device)
+        self.dtype = B.DTYPES[dtype]
+        self.tdtype = torch_dtype(self.dtype)
+        self.tree = B.TREES[tree]
+        self.tree_info = B.medusa_tree_info(self.tree)
+        self.R = B.medusa_pack_tile_rows(self.dtype)
+        self._keep: List[torch.Tensor] = []
+        self._layers: List[B.LayerWeights] = []
+        self._heads = []
+        self.embed = self.lm_head = self.g_final = None
+        self.weights: Optional[B.Weights] = None
+        self.packed_bytes = 0
+
+    # -- packing helpers -------------------------------------------------------------------------
+    def _alloc_packed(self, n_rows, k) -> torch.Tensor:
+        nbytes = B.medusa_packed_bytes(self.dtype, n_rows, k)
+        t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._keep.append(t)
+        self.packed_bytes += nbytes
+        return t
+
+    def _dev(self, t: torch.Tensor) -> torch.Tensor:
+        return t.to(self.device, self.tdtype).contiguous()
+
+    def pack(self, mats: Sequence[torch.Tensor], interleave: bool = False) -> torch.Tensor:
+        """Stacks (or tile-interleaves) row-major [n_i, k] matrices into one packed matrix."""
+        k = mats[0].shape[1]
+        total = sum(m.shape[0] for m in mats)
+        dst = self._alloc_packed(total, k)
+        off = 0
+        for i, m in enumerate(mats):
+            m = self._dev(m)
+            if interleave:
+                B.medusa_pack_weight(self.dtype, m, dst, total, i, len(mats))
+            else:
+                B.medusa_pack_weight(self.dtype, m, dst, total, off // self.R, 1)
+                off += m.shape[0]
+        torch.cuda.synchronize(self.device)          # the row-major sources may be freed by the caller now
+        return dst
+
+    def _gain(self, g) -> torch.Tensor:
+        g = self._dev(g)
+        self._keep.append(g)
+        return g
+
+    # -- model assembly --------------------------------------------------------------------------
+    def add_layer(self, wq, wk, wv, wo, wgate, wup, wdown, g_attn, g_ffn) -> None:
+        lw = B.LayerWeights(self.pack([wq, wk, wv]).data_ptr(), self.pack([wo]).data_ptr(),
+                            self.pack([wgate, wup], interleave=True).data_ptr(), self.pack([wdown]).data_ptr(),
+                            self._gain(g_attn).data_ptr(), self._gain(g_ffn).data_ptr())
+        self._layers.append(lw)
+
+    def set_embed(self, e) -> None:
+        self.embed = self._dev(e)
+
+    def set_lm_head(self, w) -> None:
+        self.lm_head = self.pack([w])
+
+    def set_final_gain(self, g) -> None:
+        self.g_final = self._gain(g)
+
+    def add_medusa_head(self, w1, b1, lm) -> None:
+        self._heads.append((self.pack([w1]), None if b1 is None else self._gain(b1), self.pack([lm])))
+
+    def finalize(self) -> "DeviceModel":
+        n = len(self._layers)
+        self._layer_arr = (B.LayerWeights * max(n, 1))(*self._layers)
+        nh = len(self._heads)
+        self._w1 = (C.c_void_p * max(nh, 1))(*[h[0].data_ptr() for h in self._heads])
+        self._lm = (C.c_void_p * max(nh, 1))(*[h[2].data_ptr() for h in self._heads])
+        has_bias = any(h[1] is not None for h in self._heads)
+        self._b1 = (C.c_void_p * max(nh, 1))(*[None if h[1] is None else h[1].data_ptr() for h in self._heads])
+        self.weights = B.Weights(
+            C.cast(self._layer_arr, C.POINTER(B.LayerWeights)),
+            None if self.embed is None else self.embed.data_ptr(),
+            None if self.lm_head is None else self.lm_head.data_ptr(),
+            None if self.g_final is None else self.g_final.data_ptr(),
+            nh, C.cast(self._w1, C.POINTER(C.c_void_p)),
+            C.cast(self._b1, C.POINTER(C.c_void_p)) if has_bias else None,
+            C.cast(self._lm, C.POINTER(C.c_void_p)))
+        return self
+
+    def layer(self, l: int) -> B.LayerWeights:
+        return self._layers[l]
+
+    def workspace(self, batch: int, max_prefix: int) -> torch.Tensor:
+        n = B.medusa_workspace_bytes(self.desc, batch, max_prefix)
+        return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+
+class DeviceKV:
+    """KV cache in the library's own layout."""
+
+    def __init__(self, model: DeviceModel, batch: int, cap: int, n_layers: Optional[int] = None):
+        d = model.desc
+        self.model = model
+        self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, d.n_heads, d.head_dim, cap, model.dtype)
+        nbytes = B.medusa_kv_bytes(self.desc)
+        self.k = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
+        self.v = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
+        self.desc.k, self.desc.v = self.k.data_ptr(), self.v.data_ptr()
+        self.bytes = 2 * nbytes
+
+    def write(self, layer: int, seq: int, pos0: int, k_rows: torch.Tensor, v_rows: torch.Tensor) -> None:
+        """k_rows, v_rows: [n_heads, n, head_dim] storage dtype."""
+        k_rows = k_rows.to(self.model.device, self.model.tdtype).contiguous()
+        v_rows = v_rows.to(self.model.device, self.model.tdtype).contiguous()
+        B.medusa_kv_write(self.desc, layer, seq, pos0, k_rows.shape[1], k_rows, v_rows)
+        torch.cuda.synchronize(self.model.device)
+
+    def read(self, layer: int, seq: int, pos0: int, n: int):
+        d = self.desc
+        k = torch.empty(d.n_heads, n, d.head_dim, dtype=self.model.tdtype, device=self.model.device)
+        v = torch.empty_like(k)
+        B.medusa_kv_read(self.desc, layer, seq, pos0, n, k, v)
+        return k, v
+
+
+class StepBuffers:
+    """Device outputs of one heads -> verify -> accept -> compact step for a batch."""
+
+    def __init__(self, model: DeviceModel, batch: int, max_prefix: int, want_logits: bool = False,
+                 want_head_logits: bool = False):
+        dev, ti, d = model.device, model.tree_info, model.desc
+        T, K = ti["T"], ti["K"]
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.batch, self.max_prefix = batch, max_prefix
+        self.ws = model.workspace(batch, max_prefix)
+        self.cand_flat = torch.zeros(batch, ti["n_cand"], **i32)
+        self.tree_tokens = torch.zeros(batch, T, **i32)
+        self.node_argmax = torch.zeros(batch, T, **i32)
+        self.hidden = torch.zeros(batch, T, d.d, dtype=model.tdtype, device=dev)
+        self.logits = torch.zeros(batch, T, d.vocab, dtype=torch.float32, device=dev) if want_logits else None
+        self.head_logits = (torch.zeros(batch, K + 1, d.vocab, dtype=torch.float32, device=dev)
+                            if want_head_logits else None)
+        self.accept_len = torch.zeros(batch, **i32)
+        self.best_path = torch.zeros(batch, **i32)
+        self.acc_nodes = torch.zeros(batch, K + 1, **i32)
+        self.acc_tokens = torch.zeros(batch, K + 1, **i32)
+        self.next_root = torch.zeros(batch, **i32)
+        self.last_node = torch.zeros(batch, **i32)
+        self.kv_src_slots = torch.zeros(batch, K + 1, **i32)
+
+
+def run_step(model: DeviceModel, kv: DeviceKV, buf: StepBuffers, hidden, src_row, root_token, seq_len,
+             with_heads: bool = True, stream=None) -> None:
+    """Enqueues heads -> verify -> accept -> compact (the four C-ABI calls, nothing else)."""
+    Bn = buf.batch
+    if with_heads:
+        B.medusa_heads(model.desc, model.weights, hidden, src_row, root_token, Bn, hidden.shape[1], buf.cand_flat,
+                       buf.tree_tokens, buf.head_logits, buf.ws, stream)
+    B.tree_verify_step(model.desc, model.weights, buf.tree_tokens, kv.desc, seq_len, Bn, buf.max_prefix,
+                       buf.node_argmax, buf.hidden, buf.logits, buf.ws, stream)
+    B.accept_longest_prefix(model.tree, buf.tree_tokens, buf.node_argmax, Bn, buf.accept_len, buf.best_path,
+                            buf.acc_nodes, buf.acc_tokens, buf.next_root, buf.last_node, stream)
+    B.kv_compact(kv.desc, model.tree, buf.acc_nodes, buf.accept_len, seq_len, buf.kv_src_slots, Bn, buf.max_prefix,
+                 stream)

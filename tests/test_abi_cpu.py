@@ -1,0 +1,68 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares, its
+compiled-in tree tables equal the oracle's, and argument errors come back as status codes (no GPU work)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workload as W
+import paper_2603_03383_amd as P
+from oracle import tree as OT
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(P.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "medusa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(?:int|int64_t|const char\*)\s+(\w+)\s*\(", text))
+    assert {"medusa_heads", "tree_verify_layer", "tree_verify_step", "accept_longest_prefix", "kv_compact"} <= declared
+    assert declared == set(P.EXPORTED)
+    lib = P.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64)], ids=["tree15", "tree64"])
+def test_compiled_tables_equal_oracle_tree(spec, tid):
+    t = P.medusa_tree_tables(tid)
+    o = OT.build_tree(spec.caps, spec.budgets)
+    assert (t["T"], t["K"], t["n_paths"], t["n_cand"], t["topk"]) == (o["T"], o["K"], len(o["retrieve"]), o["n_cand"], o["caps"])
+    assert np.array_equal(t["parent"], o["parent"])
+    assert np.array_equal(t["depth"], o["depth"])
+    assert np.array_equal(t["cand_slot"], o["cand_slot"])
+    assert np.array_equal(t["retrieve"], o["retrieve"])
+    bits = (t["anc_mask"][:, None] >> np.arange(o["T"], dtype=np.uint64)[None, :]) & np.uint64(1)
+    assert np.array_equal(bits.astype(bool), o["mask"])
+
+
+def test_argument_errors_are_status_codes():
+    m = P.ModelDesc(256, 4, 64, 688, 1024, 2, P.MDZ_FP32, P.MDZ_TREE_15, 1e-5, 1e4)
+    assert P.medusa_workspace_bytes(m, 1, 64) > 0
+    for field, bad in [("d", 255), ("dtype", 7), ("tree", 9), ("ffn", 690), ("head_dim", 0)]:
+        mm = P.ModelDesc.from_buffer_copy(m)
+        setattr(mm, field, bad)
+        with pytest.raises(P.MedusaError) as e:
+            P.medusa_workspace_bytes(mm, 1, 64)
+        assert e.value.status in (-1, -2)
+    with pytest.raises(P.MedusaError):
+        P.medusa_tree_info(5)
+    with pytest.raises(P.MedusaError):
+        P.medusa_packed_bytes(P.MDZ_BF16, 0, 16)
+    kv = P.KvDesc(None, None, 2, 1, 4, 64, 128, P.MDZ_FP32)
+    assert P.medusa_kv_bytes(kv) == 2 * 4 * 128 * 64 * 4
+    lib = P.lib()
+    # NULL buffers: rejected before anything is enqueued (safe without a GPU)
+    assert lib.accept_longest_prefix(0, None, None, 1, None, None, None, None, None, None, None) == -1
+    assert lib.kv_compact(kv, 0, None, None, None, None, 1, 10, None) == -1
+    assert b"NULL" in lib.medusa_last_error()
+    assert P.medusa_packed_bytes(P.MDZ_BF16, 4096, 4096) == 4096 * 4096 * 2
+    assert P.medusa_pack_tile_rows(P.MDZ_BF16) == 32 and P.medusa_pack_tile_rows(P.MDZ_FP32) == 16

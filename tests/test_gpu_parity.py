@@ -1,0 +1,380 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU oracle on identical
+seeded inputs.  Bit-exact for ids / lengths / indices, tolerance on floating point:
+  fp32 storage: 1e-5 x max(1, max|oracle logits|);  bf16 storage: 2e-2 x the same scale.
+Near-tie rule for ids derived from floating point: the argmax / top-k kernels are checked bit-exactly
+against the oracle's selection applied to the GPU's own logits; against the oracle's logits they must
+agree wherever the oracle's deciding gap exceeds twice the tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+import paper_2603_03383_amd as P
+from oracle import medusa as O
+from tests import gpu_util as G
+from tests import util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+
+
+def _scale(a):
+    return max(1.0, float(np.abs(a).max()))
+
+
+def _i32(a, dev=G.DEV):
+    return torch.tensor(np.asarray(a), dtype=torch.int32, device=dev)
+
+
+def check_argmax_near_tie(gpu_ids, gpu_logits, ref_logits, tol_abs):
+    """gpu_ids [R]; logits [R,V]."""
+    assert np.array_equal(gpu_ids, O.argmax_lowest(gpu_logits.astype(np.float64))), "argmax kernel != argmax of its own logits"
+    ref_ids = O.argmax_lowest(ref_logits)
+    part = np.partition(ref_logits, -2, axis=1)
+    gap = part[:, -1] - part[:, -2]
+    decided = gap > 2 * tol_abs
+    assert np.array_equal(gpu_ids[decided], ref_ids[decided])
+    for r in np.nonzero(~decided)[0]:                                  # near ties: must pick one of the tied leaders
+        assert ref_logits[r, gpu_ids[r]] >= part[r, -1] - 2 * tol_abs
+    return int((~decided).sum())
+
+
+def check_topk_near_tie(gpu_ids, gpu_logits, ref_logits, k, tol_abs):
+    assert gpu_ids.tolist() == O.topk_lowest(gpu_logits.astype(np.float64), k).tolist()
+    ref_ids = O.topk_lowest(ref_logits, k)
+    srt = np.sort(ref_logits)[::-1]
+    gaps = srt[:k] - srt[1:k + 1]
+    if (gaps > 2 * tol_abs).all():
+        assert gpu_ids.tolist() == ref_ids.tolist()
+        return 0
+    assert all(ref_logits[i] >= srt[k - 1] - 2 * tol_abs for i in gpu_ids)
+    return 1
+
+
+# ------------------------------------------------------------------------------------------------
+# config 1: tiny fp32 model, 15-node tree, causal-prefill prefix of 64 tokens — the whole path
+# ------------------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def cfg1():
+    w = W.CONFIGS["cfg1_tiny_fp32"]
+    S = w.prefix[0]
+    model = U.oracle_model(w)
+    tree = U.oracle_tree(w)
+    prefix_tokens = W.random_tokens(w, "prefix", (S,)).numpy()
+    kc, vc = O.empty_cache(model["cfg"], S + 2 * tree["T"])
+    lg, hid = O.causal_decode(prefix_tokens, model, kc, vc, 0)
+    dm = G.device_model(w)
+    return dict(w=w, S=S, model=model, tree=tree, kc=kc, vc=vc, dm=dm, last_hidden=hid[-1], last_logits=lg[-1])
+
+
+def test_cfg1_heads_verify_accept_compact(cfg1):
+    w, S, model, tree, dm = cfg1["w"], cfg1["S"], cfg1["model"], cfg1["tree"], cfg1["dm"]
+    T, K = tree["T"], tree["K"]
+    tol = TOL["fp32"]
+    h = cfg1["last_hidden"].astype(np.float32)                         # hidden after the last prefix token
+    heads = O.medusa_heads(h, model, tree)
+    kc, vc = U.copy_cache(cfg1["kc"]), U.copy_cache(cfg1["vc"])
+    ref = O.tree_verify_step(heads["tree_tokens"], model, kc, vc, S, tree)
+    acc = O.accept_longest_prefix(tree, heads["tree_tokens"], ref["node_argmax"])
+
+    kv = G.device_kv_from_oracle(dm, [cfg1["kc"]], [cfg1["vc"]], [S], cap=S + T)
+    buf = P.StepBuffers(dm, 1, S, want_logits=True, want_head_logits=True)
+    seq_len = _i32([S])
+    hid_in = torch.tensor(h, device=G.DEV).view(1, 1, -1)
+    P.run_step(dm, kv, buf, hid_in, None, None, seq_len)
+    torch.cuda.synchronize()
+
+    # heads
+    hl = buf.head_logits[0].cpu().numpy()
+    assert np.abs(hl - heads["head_logits"]).max() <= tol * _scale(heads["head_logits"])
+    assert buf.cand_flat[0].cpu().numpy().tolist() == heads["cand_flat"].tolist()
+    assert buf.tree_tokens[0].cpu().numpy().tolist() == heads["tree_tokens"].tolist()
+    # verify
+    lg = buf.logits[0].cpu().numpy()
+    assert np.abs(lg - ref["logits"]).max() <= tol * _scale(ref["logits"])
+    assert np.abs(buf.hidden[0].cpu().numpy() - ref["hidden"]).max() <= tol * _scale(ref["hidden"])
+    n_tie = check_argmax_near_tie(buf.node_argmax[0].cpu().numpy(), lg, ref["logits"], tol * _scale(ref["logits"]))
+    assert n_tie == 0
+    # accept + compact (bit exact)
+    assert int(buf.accept_len[0]) == acc["accept_len"] and int(buf.best_path[0]) == acc["best_path"]
+    assert buf.acc_nodes[0].cpu().numpy().tolist() == acc["acc_nodes"].tolist()
+    assert buf.acc_tokens[0].cpu().numpy().tolist() == acc["acc_tokens"].tolist()
+    assert int(buf.next_root[0]) == acc["next_root"] and int(buf.last_node[0]) == acc["last_node"]
+    src, S2 = O.kv_compact(kc, vc, S, acc["acc_nodes"], acc["accept_len"])
+    assert buf.kv_src_slots[0].cpu().numpy().tolist() == src.tolist() and int(seq_len[0]) == S2
+    for l in range(w.n_layers):
+        k, v = kv.read(l, 0, 0, S + T)
+        np.testing.assert_allclose(k.cpu().numpy()[:, :S2], kc[l][:, :S2], rtol=0, atol=2e-5)
+        np.testing.assert_allclose(v.cpu().numpy()[:, :S2], vc[l][:, :S2], rtol=0, atol=2e-5)
+
+
+@pytest.mark.parametrize("m", [0, 1, 2, 3])
+def test_cfg1_planted_acceptance_and_chained_step(cfg1, m):
+    """Tree tokens carry the model's own greedy continuation along one path: A must be m+1, the compacted
+    cache must equal the oracle's, and a second chained step must agree with the oracle's second step."""
+    w, S, model, tree, dm = cfg1["w"], cfg1["S"], cfg1["model"], cfg1["tree"], cfg1["dm"]
+    T, K = tree["T"], tree["K"]
+    tol = TOL["fp32"]
+    greedy = [int(np.argmax(cfg1["last_logits"]))]
+    kg, vg = U.copy_cache(cfg1["kc"]), U.copy_cache(cfg1["vc"])
+    for i in range(K + 1):
+        lg1, _ = O.causal_decode([greedy[-1]], model, kg, vg, S + i)
+        greedy.append(int(np.argmax(lg1[-1])))
+    path = [0]
+    for d in range(K):
+        path.append(max(n for n in range(T) if tree["parent"][n] == path[-1]))
+    tokens = ((np.arange(T) * 37 + 11) % w.vocab).astype(np.int32)
+    tokens[0] = greedy[0]
+    for d in range(1, m + 1):
+        tokens[path[d]] = greedy[d]
+    kc, vc = U.copy_cache(cfg1["kc"]), U.copy_cache(cfg1["vc"])
+    ref = O.tree_verify_step(tokens, model, kc, vc, S, tree)
+    for n in range(1, T):                                              # remove accidental matches elsewhere
+        if n not in path[:m + 1] and tokens[n] == ref["node_argmax"][tree["parent"][n]]:
+            tokens[n] = (tokens[n] + 1) % w.vocab
+    kc, vc = U.copy_cache(cfg1["kc"]), U.copy_cache(cfg1["vc"])
+    ref = O.tree_verify_step(tokens, model, kc, vc, S, tree)
+    acc = O.accept_longest_prefix(tree, tokens, ref["node_argmax"])
+    assert acc["accept_len"] == m + 1
+    _, S2 = O.kv_compact(kc, vc, S, acc["acc_nodes"], acc["accept_len"])
+
+    kv = G.device_kv_from_oracle(dm, [cfg1["kc"]], [cfg1["vc"]], [S], cap=S + 2 * T)
+    buf = P.StepBuffers(dm, 1, S + K + 1, want_logits=True)
+    buf.tree_tokens.copy_(_i32(tokens).view(1, T))
+    seq_len = _i32([S])
+    P.run_step(dm, kv, buf, None, None, None, seq_len, with_heads=False)
+    torch.cuda.synchronize()
+    assert int(buf.accept_len[0]) == m + 1 and int(seq_len[0]) == S2
+    assert buf.acc_nodes[0].cpu().numpy().tolist() == acc["acc_nodes"].tolist()
+    assert buf.acc_tokens[0, :m + 1].cpu().numpy().tolist() == greedy[:m + 1]
+    assert int(buf.next_root[0]) == greedy[m + 1]
+    # second, chained step: device state only (seq_len and the compacted cache stay on the GPU)
+    tokens2 = W.random_tokens(w, f"chain2.{m}", (T,)).numpy().astype(np.int32)
+    tokens2[0] = acc["next_root"]
+    ref2 = O.tree_verify_step(tokens2, model, kc, vc, S2, tree)
+    buf.tree_tokens.copy_(_i32(tokens2).view(1, T))
+    P.run_step(dm, kv, buf, None, None, None, seq_len, with_heads=False)
+    torch.cuda.synchronize()
+    assert np.abs(buf.logits[0].cpu().numpy() - ref2["logits"]).max() <= tol * _scale(ref2["logits"])
+    acc2 = O.accept_longest_prefix(tree, tokens2, ref2["node_argmax"])
+    assert int(buf.accept_len[0]) == acc2["accept_len"] and int(seq_len[0]) == S2 + acc2["accept_len"]
+
+
+# ------------------------------------------------------------------------------------------------
+# config 2: one full-size 7B-class layer, bf16, 64-node tree, prefix 512
+# ------------------------------------------------------------------------------------------------
+
+def _layer_case(w, S_list, max_prefix, x_seed="layer_x"):
+    tree = U.oracle_tree(w)
+    T = tree["T"]
+    Bn = len(S_list)
+    cfg = U.oracle_cfg(w)
+    lw = U.oracle_layer(w, 0, device=G.DEV)
+    dm = G.device_model(w.with_(vocab=1024), heads=False, n_layers=1)          # vocab irrelevant for one layer
+    kv = P.DeviceKV(dm, batch=Bn, cap=max_prefix + T, n_layers=1)
+    x = W.hidden_state(w, x_seed, Bn * T, device=G.DEV).float()                # bf16-valued fp32 rows
+    x_ref = x.cpu().numpy().astype(np.float64)
+    outs, caches = [], []
+    for b, S in enumerate(S_list):
+        k, v = W.prefix_kv(w.with_(prefix=tuple(S_list)), 0, b, G.DEV)
+        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc[:, :S] = U.to_np(k); vc[:, :S] = U.to_np(v)
+        if S:
+            kv.write(0, b, 0, k, v)
+        outs.append(O.tree_verify_layer(x_ref[b * T:(b + 1) * T], lw, kc, vc, S, tree, cfg))
+        caches.append((kc, vc))
+    ws = dm.workspace(Bn, max_prefix)
+    seq_len = _i32(S_list)
+    P.tree_verify_layer(dm.desc, dm.layer(0), 0, x, kv.desc, seq_len, Bn, max_prefix, ws)
+    torch.cuda.synchronize()
+    return dict(x=x.cpu().numpy(), ref=np.concatenate(outs), caches=caches, kv=kv, T=T)
+
+
+def _check_layer(r, S_list, dtype):
+    tol = TOL[dtype]
+    err = np.abs(r["x"] - r["ref"]).max()
+    assert err <= tol * _scale(r["ref"]), f"layer output error {err} vs scale {_scale(r['ref'])}"
+    T = r["T"]
+    for b, S in enumerate(S_list):
+        k, v = r["kv"].read(0, b, S, T)
+        kc, vc = r["caches"][b]
+        assert np.abs(U.to_np(k) - kc[:, S:]).max() <= tol * _scale(kc[:, S:])
+        assert np.abs(U.to_np(v) - vc[:, S:]).max() <= tol * _scale(vc[:, S:])
+        if S:                                                                   # prefix rows untouched, bit for bit
+            k0, v0 = r["kv"].read(0, b, 0, S)
+            assert np.array_equal(U.to_np(k0), kc[:, :S]) and np.array_equal(U.to_np(v0), vc[:, :S])
+    return err / _scale(r["ref"])
+
+
+def test_cfg2_full_size_layer_bf16():
+    w = W.CONFIGS["cfg2_layer_bf16"]
+    r = _layer_case(w, list(w.prefix), w.prefix[0])
+    rel = _check_layer(r, list(w.prefix), "bf16")
+    print(f"cfg2 layer: max error / scale = {rel:.3e}")
+
+
+@pytest.mark.parametrize("S_list,max_prefix", [([0], 0), ([1], 5), ([77], 100), ([300, 0, 45], 300)])
+def test_small_bf16_layer_ragged_and_empty_prefix(S_list, max_prefix):
+    w = W.CONFIGS["cfg2_layer_bf16"].with_(d=256, n_heads=2, head_dim=128, ffn=704, name="small_bf16")
+    r = _layer_case(w, S_list, max_prefix, x_seed=f"small_x{len(S_list)}")
+    _check_layer(r, S_list, "bf16")
+
+
+def test_layer_is_deterministic_run_to_run():
+    w = W.CONFIGS["cfg2_layer_bf16"].with_(d=512, n_heads=4, head_dim=128, ffn=1408, name="det_bf16")
+    a = _layer_case(w, [130], 130)
+    b = _layer_case(w, [130], 130)
+    assert np.array_equal(a["x"], b["x"])
+
+
+# ------------------------------------------------------------------------------------------------
+# config 3 shapes with fewer layers: full widths, vocab 128000, 4 Medusa heads, prefix 1024
+# ------------------------------------------------------------------------------------------------
+
+def test_cfg3_shapes_two_layers_full_step_bf16():
+    w = W.CONFIGS["cfg3_step_1k"].with_(n_layers=2)
+    S = w.prefix[0]
+    tol = TOL["bf16"]
+    tree = U.oracle_tree(w)
+    T, K = tree["T"], tree["K"]
+    model = U.oracle_model(w, device=G.DEV)
+    dm = G.device_model(w)
+    kc, vc = U.oracle_prefix_cache(w, 0, S + T, device=G.DEV)
+    kv = G.device_kv_random_prefix(dm, w, cap=S + T)
+    h = W.hidden_state(w, "heads_in", 1, device=G.DEV)
+    heads = O.medusa_heads(U.to_np(h)[0], model, tree)
+
+    buf = P.StepBuffers(dm, 1, S, want_logits=True, want_head_logits=True)
+    seq_len = _i32([S])
+    P.run_step(dm, kv, buf, h.view(1, 1, -1), None, None, seq_len)
+    torch.cuda.synchronize()
+
+    hl = buf.head_logits[0].cpu().numpy()
+    hscale = _scale(heads["head_logits"])
+    assert np.abs(hl - heads["head_logits"]).max() <= tol * hscale
+    cand = buf.cand_flat[0].cpu().numpy()
+    assert check_argmax_near_tie(cand[:1], hl[:1], heads["head_logits"][:1], tol * hscale) == 0
+    off, ties = 1, 0
+    for k in range(K):
+        c = tree["caps"][k]
+        ties += check_topk_near_tie(cand[off:off + c], hl[k + 1], heads["head_logits"][k + 1], c, tol * hscale)
+        off += c
+    gpu_tokens = buf.tree_tokens[0].cpu().numpy()
+    assert gpu_tokens.tolist() == cand[tree["cand_slot"]].tolist()
+    if ties == 0:
+        assert gpu_tokens.tolist() == heads["tree_tokens"].tolist()
+
+    # verify on the GPU's own tree tokens (identical inputs for the discrete stages)
+    ref = O.tree_verify_step(gpu_tokens, model, kc, vc, S, tree)
+    lg = buf.logits[0].cpu().numpy()
+    lscale = _scale(ref["logits"])
+    err = np.abs(lg - ref["logits"]).max()
+    print(f"cfg3/2 layers: logits err/scale {err / lscale:.3e}, head logits err/scale "
+          f"{np.abs(hl - heads['head_logits']).max() / hscale:.3e}")
+    assert err <= tol * lscale
+    assert np.abs(U.to_np(buf.hidden[0]) - ref["hidden"]).max() <= tol * _scale(ref["hidden"])
+    gpu_am = buf.node_argmax[0].cpu().numpy()
+    check_argmax_near_tie(gpu_am, lg, ref["logits"], tol * lscale)
+    acc = O.accept_longest_prefix(tree, gpu_tokens, gpu_am)                   # oracle rule on the GPU's ids
+    assert int(buf.accept_len[0]) == acc["accept_len"] and int(buf.best_path[0]) == acc["best_path"]
+    assert buf.acc_nodes[0].cpu().numpy().tolist() == acc["acc_nodes"].tolist()
+    assert buf.acc_tokens[0].cpu().numpy().tolist() == acc["acc_tokens"].tolist()
+    assert int(seq_len[0]) == S + acc["accept_len"]
+    assert buf.kv_src_slots[0].cpu().numpy().tolist() == [S + n if n >= 0 else -1 for n in acc["acc_nodes"]]
+
+
+# ------------------------------------------------------------------------------------------------
+# integer kernels in isolation: bit exact
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64)], ids=["tree15", "tree64"])
+@pytest.mark.parametrize("vocab", [2, 3, 5, 1000])
+def test_accept_fuzz_bit_exact(spec, tid, vocab):
+    from oracle import tree as OT
+    tree = OT.build_tree(spec.caps, spec.budgets)
+    T, K = tree["T"], tree["K"]
+    Bn = 257
+    toks = W.uniform_int(21, f"g.acc.tok.{spec.name}.{vocab}", (Bn, T), 0, vocab)
+    ams = W.uniform_int(21, f"g.acc.am.{spec.name}.{vocab}", (Bn, T), 0, vocab)
+    dev = lambda *s: torch.zeros(*s, dtype=torch.int32, device=G.DEV)
+    out = dict(accept_len=dev(Bn), best_path=dev(Bn), acc_nodes=dev(Bn, K + 1), acc_tokens=dev(Bn, K + 1),
+               next_root=dev(Bn), last_node=dev(Bn))
+    P.accept_longest_prefix(tid, toks.to(G.DEV), ams.to(G.DEV), Bn, **out)
+    torch.cuda.synchronize()
+    out = {k: v.cpu().numpy() for k, v in out.items()}
+    for b in range(Bn):
+        a = O.accept_longest_prefix(tree, toks[b].numpy(), ams[b].numpy())
+        assert out["accept_len"][b] == a["accept_len"] and out["best_path"][b] == a["best_path"]
+        assert out["acc_nodes"][b].tolist() == a["acc_nodes"].tolist()
+        assert out["acc_tokens"][b].tolist() == a["acc_tokens"].tolist()
+        assert out["next_root"][b] == a["next_root"] and out["last_node"][b] == a["last_node"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_kv_compact_bit_exact_ragged_batch(dtype):
+    from oracle import tree as OT
+    spec = W.TREE64
+    tree = OT.build_tree(spec.caps, spec.budgets)
+    T, K = tree["T"], tree["K"]
+    L, H, hd, Bn = 3, 2, 128, 5
+    S_list = [0, 7, 33, 100, 64]
+    max_prefix = 100
+    cap = max_prefix + T
+    dm = P.DeviceModel(d=H * hd, n_heads=H, head_dim=hd, ffn=64, vocab=64, n_layers=L, dtype=dtype, tree="tree64")
+    kv = P.DeviceKV(dm, batch=Bn, cap=cap)
+    kcs, vcs = [], []
+    for b in range(Bn):
+        kb, vb = [], []
+        for l in range(L):
+            k = W.normal(5, f"cmp.k.{b}.{l}", (H, cap, hd), 1.0, dm.tdtype)
+            v = W.normal(5, f"cmp.v.{b}.{l}", (H, cap, hd), 1.0, dm.tdtype)
+            kv.write(l, b, 0, k, v)
+            kb.append(U.to_np(k).astype(np.float64)); vb.append(U.to_np(v).astype(np.float64))
+        kcs.append(kb); vcs.append(vb)
+    # accepted chains of every length, taken from retrieve rows
+    rows = [0, 37, 20, 30, 36]
+    lens = [1, 5, 3, 4, 2]
+    acc_nodes = np.full((Bn, K + 1), -1, np.int32)
+    for b in range(Bn):
+        A = min(lens[b], int((tree["retrieve"][rows[b]] >= 0).sum()))
+        lens[b] = A
+        acc_nodes[b, :A] = tree["retrieve"][rows[b], :A]
+    seq_len = _i32(S_list)
+    slots = torch.zeros(Bn, K + 1, dtype=torch.int32, device=G.DEV)
+    P.kv_compact(kv.desc, P.MDZ_TREE_64, _i32(acc_nodes), _i32(lens), seq_len, slots, Bn, max_prefix)
+    torch.cuda.synchronize()
+    for b in range(Bn):
+        src, S2 = O.kv_compact(kcs[b], vcs[b], S_list[b], acc_nodes[b], lens[b])
+        assert slots[b].cpu().numpy().tolist() == src.tolist() and int(seq_len[b]) == S2
+        for l in range(L):
+            k, v = kv.read(l, b, 0, cap)
+            assert np.array_equal(U.to_np(k), kcs[b][l]) and np.array_equal(U.to_np(v), vcs[b][l])
+
+
+def test_empty_batch_and_bad_arguments():
+    w = W.CONFIGS["cfg1_tiny_fp32"]
+    dm = G.device_model(w)
+    kv = P.DeviceKV(dm, batch=1, cap=64 + 15)
+    buf = P.StepBuffers(dm, 1, 64)
+    seq_len = _i32([64])
+    # B = 0: accepted, nothing happens
+    P.tree_verify_step(dm.desc, dm.weights, buf.tree_tokens, kv.desc, seq_len, 0, 64, buf.node_argmax, None, None, buf.ws)
+    P.accept_longest_prefix(dm.tree, buf.tree_tokens, buf.node_argmax, 0, buf.accept_len, buf.best_path, buf.acc_nodes,
+                            buf.acc_tokens, buf.next_root, buf.last_node)
+    P.kv_compact(kv.desc, dm.tree, buf.acc_nodes, buf.accept_len, seq_len, buf.kv_src_slots, 0, 64)
+    # prefix bound beyond the cache, workspace too small, batch beyond the cache
+    with pytest.raises(P.MedusaError) as e:
+        P.tree_verify_step(dm.desc, dm.weights, buf.tree_tokens, kv.desc, seq_len, 1, 65, buf.node_argmax, None, None, buf.ws)
+    assert e.value.status == -2
+    with pytest.raises(P.MedusaError) as e:
+        P.tree_verify_step(dm.desc, dm.weights, buf.tree_tokens, kv.desc, seq_len, 1, 64, buf.node_argmax, None, None,
+                           buf.ws[:1024])
+    assert e.value.status == -4
+    with pytest.raises(P.MedusaError) as e:
+        P.tree_verify_step(dm.desc, dm.weights, buf.tree_tokens, kv.desc, seq_len, 2, 64, buf.node_argmax, None, None, buf.ws)
+    assert e.value.status == -2
+    torch.cuda.synchronize()
+    assert int(seq_len[0]) == 64
