@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the Medusa static-tree verify step on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of seeded synthetic input, all four C-ABI
+calls: medusa_heads -> tree_verify_step -> accept_longest_prefix -> kv_compact, inputs resident in HBM.
+Prints ONE JSON line: steps/s (value), ms/step, achieved HBM GB/s of the whole step, a `roofline`
+object for the dominant kernel family (the weight-streaming GEMMs, timed with HIP events on the launch
+stream in instrumented steps that follow the timed region) and a `cpu_baseline` object (the float64
+oracle timed on this machine's host cores on a bounded sample of the same workload).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_step_1k] [--no-heads]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(w, with_heads: bool):
+    """Bytes one step must move through HBM: every weight once, the prefix KV once, the T new KV rows
+    written and read once, the embedding rows gathered.  Activations (<= 1.4 MB each) are not counted."""
+    es = 2 if w.dtype == "bf16" else 4
+    T, K = w.tree.n_nodes, w.n_medusa
+    layer_w = (4 * w.d * w.d + 3 * w.d * w.ffn) * es
+    gemm_layers = w.n_layers * layer_w
+    lm = w.vocab * w.d * es
+    heads = K * (w.d * w.d + w.vocab * w.d) * es if with_heads else 0
+    kv_row = 2 * w.n_heads * w.head_dim * es                      # K and V of one slot, one layer
+    kv_prefix = sum(w.prefix) * kv_row * w.n_layers
+    kv_tree = 2 * w.batch * T * kv_row * w.n_layers               # written + read
+    embed = w.batch * T * w.d * es
+    return dict(gemm=gemm_layers + lm + heads, weights_layers=gemm_layers, lm_head=lm, heads=heads,
+                kv_prefix=kv_prefix, kv_tree=kv_tree, embed=embed,
+                total=gemm_layers + lm + heads + kv_prefix + kv_tree + embed)
+
+
+def build_device(w, with_heads):
+    import torch
+    import workload as W
+    import paper_2603_03383_amd as P
+    dev = "cuda:0"
+    dm = P.DeviceModel(d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn, vocab=w.vocab, n_layers=w.n_layers,
+                       dtype=w.dtype, tree=w.tree.name, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev)
+    for l in range(w.n_layers):
+        mats = [W.layer_weight(w, l, m, dev) for m in W.LAYER_MATS]
+        dm.add_layer(*mats, W.norm_gain(w, "g", dev), W.norm_gain(w, "g", dev))
+        del mats
+    dm.set_embed(W.embedding(w, dev))
+    dm.set_lm_head(W.lm_head(w, dev))
+    dm.set_final_gain(W.norm_gain(w, "g", dev))
+    if with_heads:
+        for k in range(1, w.n_medusa + 1):
+            dm.add_medusa_head(W.medusa_w1(w, k, dev), None, W.medusa_lm(w, k, dev))
+    dm.finalize()
+    max_prefix = max(w.prefix) + (w.n_medusa + 1)
+    kv = P.DeviceKV(dm, batch=w.batch, cap=max_prefix + w.tree.n_nodes)
+    for b in range(w.batch):
+        for l in range(w.n_layers):
+            k, v = W.prefix_kv(w, l, b, dev)
+            kv.write(l, b, 0, k, v)
+    torch.cuda.empty_cache()
+    return dm, kv, max_prefix
+
+
+def cpu_baseline(w, with_heads, budget_layers=2):
+    """Times the oracle (as it stands) on a bounded sample: `budget_layers` decoder layers + final norm /
+    LM head / argmax (+ one Medusa head), then scales linearly to the full step."""
+    import numpy as np
+    import workload as W
+    from oracle import medusa as O
+    from oracle import tree as OT
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    f32 = lambda t: t.detach().to("cpu").float().numpy()
+    tree = OT.build_tree(w.tree.caps, w.tree.budgets)
+    T = tree["T"]
+    cfg = dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn, vocab=w.vocab,
+               rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype)
+    gen = "cuda:0"
+    S = w.prefix[0]
+    nl = min(budget_layers, w.n_layers)
+    x = f32(W.hidden_state(w, "bench_x", T, gen)).astype(np.float64)
+    layers, caches = [], []
+    for l in range(nl):
+        lw = {m: f32(W.layer_weight(w, l, m, gen)) for m in W.LAYER_MATS}
+        lw["g_attn"] = lw["g_ffn"] = np.ones(w.d, np.float32)
+        k, v = W.prefix_kv(w, l, 0, gen)
+        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc[:, :S] = f32(k); vc[:, :S] = f32(v)
+        layers.append(lw); caches.append((kc, vc))
+    t0 = time.perf_counter()
+    for lw, (kc, vc) in zip(layers, caches):
+        x = O.tree_verify_layer(x, lw, kc, vc, S, tree, cfg)
+    t_layers = time.perf_counter() - t0
+    del layers, caches
+    model = dict(cfg=cfg, g_final=np.ones(w.d, np.float32), lm_head=f32(W.lm_head(w, gen)))
+    t0 = time.perf_counter()
+    hidden, logits = O._final(x, model)
+    am = O.argmax_lowest(logits)
+    tokens = np.arange(T) % w.vocab
+    O.accept_longest_prefix(tree, tokens, am)
+    t_final = time.perf_counter() - t0
+    t_head = 0.0
+    if with_heads:
+        head = dict(w1=f32(W.medusa_w1(w, 1, gen)), b1=None, lm=f32(W.medusa_lm(w, 1, gen)))
+        m1 = dict(model, medusa=[head])
+        tr1 = dict(tree, caps=tree["caps"][:1], cand_slot=np.zeros(T, np.int32))
+        t0 = time.perf_counter()
+        O.medusa_heads(hidden[0], m1, tr1)
+        t_head = (time.perf_counter() - t0) / 2.0          # the call also evaluates the base head: ~half is the head
+    per_seq = t_layers / nl * w.n_layers + t_final + t_head * w.n_medusa
+    est = per_seq * w.batch
+    return dict(value=1.0 / est, unit="steps/s", cores=int(cores), kind="oracle",
+                sample=f"sequence 0: {nl} of {w.n_layers} layers ({t_layers:.2f} s) + final norm/LM head/argmax/accept "
+                       f"({t_final:.2f} s)" + (f" + 1 of {w.n_medusa} Medusa heads ({t_head:.2f} s)" if with_heads else "")
+                       + f", scaled linearly to the full step of {w.batch} sequence(s): {est:.1f} s/step")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3_step_1k")
+    ap.add_argument("--no-heads", action="store_true", help="time verify+accept+compact only")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload as W
+    import paper_2603_03383_amd as P
+
+    w = W.CONFIGS[args.workload]
+    with_heads = not args.no_heads and w.n_layers > 1
+    P.lib()                                         # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dm, kv, max_prefix = build_device(w, with_heads)
+    Bn, T = w.batch, w.tree.n_nodes
+    buf = P.StepBuffers(dm, Bn, max_prefix)
+    seq0 = torch.tensor(w.prefix, dtype=torch.int32, device=dm.device)
+    seq_len = seq0.clone()
+    hidden = W.hidden_state(w, "bench_h", Bn, dm.device).view(Bn, 1, w.d)
+    root = W.random_tokens(w, "bench_root", (Bn,), dm.device)
+    buf.tree_tokens.copy_(W.random_tokens(w, "bench_tree", (Bn, T), dm.device))
+    layer_only = w.n_layers == 1
+    x0 = W.hidden_state(w, "bench_x", Bn * T, dm.device).float()
+    x = x0.clone()
+
+    def one_step():
+        seq_len.copy_(seq0)                        # compaction advanced the lengths: reset (4*B bytes)
+        if layer_only:
+            P.tree_verify_layer(dm.desc, dm.layer(0), 0, x, kv.desc, seq_len, Bn, max_prefix, buf.ws)
+        else:
+            P.run_step(dm, kv, buf, hidden, None, root, seq_len, with_heads=with_heads)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+
+    # instrumented steps: HIP events around every kernel launch, on the launch stream
+    P.medusa_profile_begin(args.steps * (w.n_layers * 12 + 64))
+    for _ in range(args.steps):
+        one_step()
+    prof = P.medusa_profile_end()
+    torch.cuda.synchronize()
+
+    ab = algorithmic_bytes(w, with_heads)
+    if layer_only:
+        ab["gemm"] = ab["weights_layers"]
+        ab["total"] = ab["weights_layers"] + ab["kv_prefix"] + ab["kv_tree"]
+    gemm = prof.get("gemm", dict(launches=0, total_us=0.0))
+    gemm_us_per_step = gemm["total_us"] / args.steps
+    gemm_gbps = ab["gemm"] / (gemm_us_per_step * 1e-6) / 1e9 if gemm_us_per_step else 0.0
+    step_gbps = ab["total"] / (ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "tree_verify_steps_per_s", "value": 1e3 / ms, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "tree_nodes": T, "prefix": list(w.prefix), "batch": Bn,
+                   "layers": w.n_layers, "with_medusa_heads": with_heads,
+                   "step": "tree_verify_layer" if layer_only else "medusa_heads+tree_verify_step+accept_longest_prefix+kv_compact"},
+        "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
+                "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
+                "kv_share_of_bytes": (ab["kv_prefix"] + ab["kv_tree"]) / ab["total"]},
+        "roofline": {"kernel": "gemm (all weight-streaming GEMM launches of a step)", "bound": "hbm",
+                     "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gemm_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_step": ab["gemm"], "launches_per_step": gemm["launches"] / args.steps,
+                     "avg_launch_us": gemm["total_us"] / max(1, gemm["launches"])},
+        "kernel_us_per_step": {k: v["total_us"] / args.steps for k, v in prof.items()},
+        "paper_context": "paper reports only ratios: 1.35x end-to-end on an NPU, fp16, L=128 (not comparable)",
+    }
+    if not args.skip_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, with_heads)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -111,6 +111,18 @@ int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_
 /* Never NULL; thread-local; valid until the next failing call on this thread. */
 const char* medusa_last_error(void);
 
+/* ---- optional per-kernel timing (benchmarks only) ---------------------------------------------- */
+
+/* Starts recording a HIP-event pair on the caller's stream around every kernel launch the library makes,
+ * for at most max_launches launches (further ones are counted as dropped).  Creates its events here, so
+ * hot-path calls still allocate nothing.  Process-global; not thread-safe. */
+int medusa_profile_begin(int max_launches);
+
+/* Stops recording, waits for the recorded events, and writes one text line per kernel family into the HOST
+ * buffer `report`: "name,launches,total_us,min_us,max_us\n" (families: gemm, attention, rmsnorm, rope,
+ * swiglu, embed, select, accept, kv_compact, misc). */
+int medusa_profile_end(char* report, int64_t report_bytes);
+
 /* ---- weight packing (one-time, outside any timed region) ------------------------------------ */
 
 /* Rows per packed tile for a dtype (32 for bf16, 16 for fp32). */

@@ -58,6 +58,8 @@ _SIGNATURES = {
     "medusa_tree_info": (C.c_int, [C.c_int] + [C.c_void_p] * 5),
     "medusa_tree_tables": (C.c_int, [C.c_int] + [C.c_void_p] * 5),
     "medusa_last_error": (C.c_char_p, []),
+    "medusa_profile_begin": (C.c_int, [C.c_int]),
+    "medusa_profile_end": (C.c_int, [C.c_char_p, C.c_int64]),
     "medusa_pack_tile_rows": (C.c_int, [C.c_int]),
     "medusa_packed_bytes": (C.c_int64, [C.c_int, C.c_int64, C.c_int64]),
     "medusa_pack_weight": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
@@ -139,6 +141,21 @@ def medusa_tree_tables(tree: int) -> dict:
     _check(lib().medusa_tree_tables(tree, parent.ctypes.data, depth.ctypes.data, cand_slot.ctypes.data,
                                     anc.ctypes.data, retrieve.ctypes.data))
     return dict(info, parent=parent, depth=depth, cand_slot=cand_slot, anc_mask=anc, retrieve=retrieve)
+
+
+def medusa_profile_begin(max_launches: int) -> None:
+    _check(lib().medusa_profile_begin(max_launches))
+
+
+def medusa_profile_end() -> dict:
+    """{family: dict(launches, total_us, min_us, max_us)}"""
+    buf = C.create_string_buffer(4096)
+    _check(lib().medusa_profile_end(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, n, tot, mn, mx = line.split(",")
+        out[name] = dict(launches=int(n), total_us=float(tot), min_us=float(mn), max_us=float(mx))
+    return out
 
 
 def medusa_pack_tile_rows(dtype: int) -> int:

@@ -90,6 +90,7 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(int tree, const T* __
 int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
                              int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                              hipStream_t st) {
+  ProfScope prof_(PROF_ATTN, st);
   const TreeTables* t = host_tree(tree);
   if (B == 0) return MDZ_OK;
   MDZ_REQUIRE(g.head_dim <= 256, MDZ_EUNSUPPORTED, "attention: head_dim %d > 256", g.head_dim);

@@ -33,6 +33,7 @@ __global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restr
 
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
                  hipStream_t st) {
+  ProfScope prof_(PROF_EMBED, st);
   if (rows == 0) return MDZ_OK;
   if (dtype == MDZ_BF16)
     embed_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t*)embed, tokens, x, d, vocab);
@@ -56,6 +57,7 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
 }
 
 int launch_rmsnorm(int dtype, const float* x, const void* g, void* xn, int rows, int d, float eps, hipStream_t st) {
+  ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
   if (dtype == MDZ_BF16)
     rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, (const bf16_t*)g, (bf16_t*)xn, d, eps);
@@ -83,6 +85,7 @@ __global__ void rope_table_kernel(int tree, const int32_t* __restrict__ seq_len,
 
 int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
                       float* cs, hipStream_t st) {
+  ProfScope prof_(PROF_ROPE, st);
   const TreeTables* t = host_tree(tree);
   int half = head_dim / 2;
   int total = B * t->T * half;
@@ -124,6 +127,7 @@ __global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, con
 int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, void* q_out, const KvGeom& g,
                         void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
                         hipStream_t st) {
+  ProfScope prof_(PROF_ROPE, st);
   const TreeTables* t = host_tree(tree);
   if (B == 0) return MDZ_OK;
   dim3 grid(B * t->T, g.n_heads);
@@ -154,6 +158,7 @@ __global__ void swiglu_kernel(const float* __restrict__ gu, T* __restrict__ u, i
 }
 
 int launch_swiglu(int dtype, const float* gu, void* u, int M, int F, hipStream_t st) {
+  ProfScope prof_(PROF_SWIGLU, st);
   int64_t total = (int64_t)M * F;
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
@@ -176,6 +181,7 @@ __global__ void gather_rows_kernel(const T* __restrict__ hidden, const int32_t* 
 
 int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, int B, int Tsrc, int d, void* h,
                        hipStream_t st) {
+  ProfScope prof_(PROF_MISC, st);
   if (B == 0) return MDZ_OK;
   if (dtype == MDZ_BF16)
     gather_rows_kernel<bf16_t><<<B, 256, 0, st>>>((const bf16_t*)hidden, src_row, Tsrc, d, (bf16_t*)h);
@@ -196,6 +202,7 @@ __global__ void head_residual_kernel(const T* __restrict__ h, const float* __res
 
 int launch_head_residual(int dtype, const void* h, const float* pre, const void* b1, void* z, int B, int d,
                          hipStream_t st) {
+  ProfScope prof_(PROF_MISC, st);
   int64_t n = (int64_t)B * d;
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
@@ -214,6 +221,7 @@ __global__ void store_rows_kernel(const float* __restrict__ src, T* __restrict__
 }
 
 int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st) {
+  ProfScope prof_(PROF_MISC, st);
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
   if (dtype == MDZ_BF16)

@@ -54,6 +54,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(const T* __restrict__
 
 int launch_gemm_generic(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy,
                         bool accumulate, hipStream_t st) {
+  ProfScope prof_(PROF_GEMM, st);
   if (M == 0 || N == 0) return MDZ_OK;
   dim3 grid((N + 63) / 64, (M + 63) / 64);
   if (dtype == MDZ_BF16)

@@ -2,6 +2,7 @@
 // Every function enqueues on `st` and returns an mdz_status.  All pointers are device pointers.
 #pragma once
 #include "common.h"
+#include "profile.h"
 
 namespace mdz {
 

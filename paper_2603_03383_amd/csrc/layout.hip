@@ -19,6 +19,7 @@ __global__ void pack_weight_kernel(const T* __restrict__ src, int64_t n_rows, in
 
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, hipStream_t st) {
+  ProfScope prof_(PROF_MISC, st);
   const int R = dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
   const int64_t kp = dtype == MDZ_BF16 ? Packed<bf16_t>::padded_k(k) : k;
   const int64_t n_pad = round_up(n_rows, R);
@@ -67,6 +68,7 @@ __global__ void kv_copy_kernel(KvGeom g, T* kc, T* vc, int layer, int seq, int p
 
 int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n,
                    void* k_rows, void* v_rows, bool to_cache, hipStream_t st) {
+  ProfScope prof_(PROF_MISC, st);
   if (n == 0) return MDZ_OK;
   int64_t total = (int64_t)g.n_heads * n * g.head_dim;
   int threads = 256;
@@ -126,6 +128,7 @@ __global__ void kv_compact_finish_kernel(int tree, const int32_t* __restrict__ a
 int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, const int32_t* acc_nodes,
                       const int32_t* accept_len, int32_t* seq_len, int32_t* kv_src_slots, int B, int max_prefix,
                       hipStream_t st) {
+  ProfScope prof_(PROF_COMPACT, st);
   if (B == 0) return MDZ_OK;
   int64_t cols = (int64_t)g.n_layers * g.n_heads * g.head_dim;
   int threads = 256;

@@ -1,0 +1,39 @@
+// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch.
+// Off by default (a single predictable branch per launch).  medusa_profile_begin creates the event
+// pool, so no hot-path call ever creates an event.  Process-global: meant for a benchmark's own thread.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace mdz {
+
+enum ProfTag {
+  PROF_GEMM = 0,     // weight-streaming GEMMs (all shapes)
+  PROF_ATTN,         // tree-masked attention (+ its combine pass)
+  PROF_NORM,         // RMSNorm
+  PROF_ROPE,         // RoPE table, RoPE + KV write
+  PROF_SWIGLU,
+  PROF_EMBED,
+  PROF_SELECT,       // argmax / top-k / candidate gather
+  PROF_ACCEPT,
+  PROF_COMPACT,
+  PROF_MISC,
+  PROF_NUM_TAGS
+};
+
+const char* prof_tag_name(int tag);
+bool prof_enabled();
+void prof_record(int tag, hipStream_t st, bool start);
+
+struct ProfScope {
+  int tag;
+  hipStream_t st;
+  bool on;
+  ProfScope(int tag_, hipStream_t st_) : tag(tag_), st(st_), on(prof_enabled()) {
+    if (on) prof_record(tag, st, true);
+  }
+  ~ProfScope() {
+    if (on) prof_record(tag, st, false);
+  }
+};
+
+}  // namespace mdz

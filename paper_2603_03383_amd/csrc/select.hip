@@ -68,6 +68,7 @@ __global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ log
 
 int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld,
                 hipStream_t st) {
+  ProfScope prof_(PROF_SELECT, st);
   if (rows == 0 || k == 0) return MDZ_OK;
   topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
   MDZ_LAUNCH_CHECK();
@@ -85,6 +86,7 @@ __global__ void scatter_i32_kernel(const int32_t* __restrict__ src, int32_t* __r
 }
 
 int launch_scatter_i32(const int32_t* src, int32_t* dst, int n, int64_t dst_stride, hipStream_t st) {
+  ProfScope prof_(PROF_SELECT, st);
   if (n == 0) return MDZ_OK;
   scatter_i32_kernel<<<(n + 63) / 64, 64, 0, st>>>(src, dst, n, dst_stride);
   MDZ_LAUNCH_CHECK();
@@ -101,6 +103,7 @@ __global__ void tree_tokens_kernel(int tree, const int32_t* __restrict__ cand_fl
 }
 
 int launch_tree_tokens(int tree, const int32_t* cand_flat, int32_t* tree_tokens, int B, hipStream_t st) {
+  ProfScope prof_(PROF_SELECT, st);
   const TreeTables* t = host_tree(tree);
   int total = B * t->T;
   if (total == 0) return MDZ_OK;
@@ -153,6 +156,7 @@ __global__ void __launch_bounds__(64) accept_kernel(int tree, const int32_t* __r
 int launch_accept(int tree, const int32_t* tree_tokens, const int32_t* node_argmax, int B, int32_t* accept_len,
                   int32_t* best_path, int32_t* acc_nodes, int32_t* acc_tokens, int32_t* next_root,
                   int32_t* last_node, hipStream_t st) {
+  ProfScope prof_(PROF_ACCEPT, st);
   if (B == 0) return MDZ_OK;
   accept_kernel<<<B, 64, 0, st>>>(tree, tree_tokens, node_argmax, accept_len, best_path, acc_nodes, acc_tokens,
                                   next_root, last_node);
