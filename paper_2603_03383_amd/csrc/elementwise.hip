@@ -43,26 +43,41 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
   return MDZ_OK;
 }
 
+// x[r] += sum_s P[s][r] (fixed order s = 0..n_part-1), then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g.
+// Either half is optional: P == nullptr skips the residual update, xn == nullptr skips the norm.
 template <typename T>
-__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ g,
-                                                      T* __restrict__ xn, int d, float eps) {
+__global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ P,
+                                                               int n_part, int64_t part_stride, int64_t ldp,
+                                                               const T* __restrict__ g, T* __restrict__ xn, int d,
+                                                               float eps) {
   __shared__ float red[4];
   int r = blockIdx.x;
-  const float* xr = x + (int64_t)r * d;
+  float* xr = x + (int64_t)r * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) ss += xr[i] * xr[i];
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = xr[i];
+    if (P) {
+      for (int s = 0; s < n_part; ++s) v += P[(int64_t)s * part_stride + (int64_t)r * ldp + i];
+      xr[i] = v;
+    }
+    ss += v * v;
+  }
+  if (!xn) return;
   ss = block_sum_256(ss, red);
   float rs = 1.0f / sqrtf(ss / (float)d + eps);
   for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
 }
 
-int launch_rmsnorm(int dtype, const float* x, const void* g, void* xn, int rows, int d, float eps, hipStream_t st) {
+int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
+                            float eps, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
   if (dtype == MDZ_BF16)
-    rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, (const bf16_t*)g, (bf16_t*)xn, d, eps);
+    residual_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const bf16_t*)g,
+                                                          (bf16_t*)xn, d, eps);
   else
-    rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, (const float*)g, (float*)xn, d, eps);
+    residual_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const float*)g,
+                                                         (float*)xn, d, eps);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -98,7 +113,8 @@ int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, i
 
 // grid (B*T, n_heads), block = head_dim/2 threads... generalised: threads stride over i < half.
 template <typename T>
-__global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, const float* __restrict__ cs,
+__global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, int n_part, int64_t part_stride,
+                                    const float* __restrict__ cs,
                                     T* __restrict__ q_out, KvGeom g, T* __restrict__ kc, T* __restrict__ vc, int layer,
                                     const int32_t* __restrict__ seq_len, int max_prefix) {
   const TreeTables& t = c_trees[tree];
@@ -109,22 +125,26 @@ __global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, con
   int S = min(max(seq_len[b], 0), max_prefix);
   int slot = S + n;
   const float* qr = qkv + (int64_t)row * 3 * d + h * hd;
-  const float* kr = qr + d;
-  const float* vr = qr + 2 * d;
+  auto rd = [&](int col) {  // fixed-order sum of the split-K partials
+    float v = 0.f;
+    for (int p = 0; p < n_part; ++p) v += qr[(int64_t)p * part_stride + col];
+    return v;
+  };
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
     float c = cs[((int64_t)row * half + i) * 2], s = cs[((int64_t)row * half + i) * 2 + 1];
-    float qa = qr[i], qb = qr[i + half];
-    float ka = kr[i], kb = kr[i + half];
+    float qa = rd(i), qb = rd(i + half);
+    float ka = rd(d + i), kb = rd(d + i + half);
+    float va = rd(2 * d + i), vb = rd(2 * d + i + half);
     q_out[(int64_t)row * d + h * hd + i] = from_float<T>(qa * c - qb * s);
     q_out[(int64_t)row * d + h * hd + i + half] = from_float<T>(qb * c + qa * s);
     kc[k_index(g, layer, b, h, slot, i)] = from_float<T>(ka * c - kb * s);
     kc[k_index(g, layer, b, h, slot, i + half)] = from_float<T>(kb * c + ka * s);
-    vc[v_index(g, layer, b, h, slot, i)] = from_float<T>(vr[i]);
-    vc[v_index(g, layer, b, h, slot, i + half)] = from_float<T>(vr[i + half]);
+    vc[v_index(g, layer, b, h, slot, i)] = from_float<T>(va);
+    vc[v_index(g, layer, b, h, slot, i + half)] = from_float<T>(vb);
   }
 }
 
-int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, void* q_out, const KvGeom& g,
+int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* cs, void* q_out, const KvGeom& g,
                         void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
                         hipStream_t st) {
   ProfScope prof_(PROF_ROPE, st);
@@ -133,10 +153,10 @@ int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, 
   dim3 grid(B * t->T, g.n_heads);
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
   if (dtype == MDZ_BF16)
-    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
+    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv.p, qkv.n, qkv.stride, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
                                                           layer, seq_len, max_prefix);
   else
-    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv, cs, (float*)q_out, g, (float*)kc, (float*)vc,
+    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv.p, qkv.n, qkv.stride, cs, (float*)q_out, g, (float*)kc, (float*)vc,
                                                          layer, seq_len, max_prefix);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
@@ -146,26 +166,31 @@ __device__ inline float silu_f(float v) { return v / (1.0f + expf(-v)); }
 
 // gate feature f sits at column (2*(f/R))*R + f%R of gu, up at (2*(f/R)+1)*R + f%R (R = tile rows)
 template <typename T>
-__global__ void swiglu_kernel(const float* __restrict__ gu, T* __restrict__ u, int M, int F) {
+__global__ void swiglu_kernel(const float* __restrict__ gu, int n_part, int64_t part_stride, T* __restrict__ u, int M,
+                              int F) {
   constexpr int R = Packed<T>::kTileRows;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)M * F) return;
   int f = idx % F;
   int64_t m = idx / F;
   int64_t col = (int64_t)(2 * (f / R)) * R + f % R;
-  float gv = gu[m * 2 * F + col], uv = gu[m * 2 * F + col + R];
+  float gv = 0.f, uv = 0.f;
+  for (int p = 0; p < n_part; ++p) {
+    gv += gu[(int64_t)p * part_stride + m * 2 * F + col];
+    uv += gu[(int64_t)p * part_stride + m * 2 * F + col + R];
+  }
   u[idx] = from_float<T>(silu_f(gv) * uv);
 }
 
-int launch_swiglu(int dtype, const float* gu, void* u, int M, int F, hipStream_t st) {
+int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStream_t st) {
   ProfScope prof_(PROF_SWIGLU, st);
   int64_t total = (int64_t)M * F;
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == MDZ_BF16)
-    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);
+    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu.p, gu.n, gu.stride, (bf16_t*)u, M, F);
   else
-    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu, (float*)u, M, F);
+    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu.p, gu.n, gu.stride, (float*)u, M, F);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -192,24 +217,29 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
 }
 
 template <typename T>
-__global__ void head_residual_kernel(const T* __restrict__ h, const float* __restrict__ pre, const T* __restrict__ b1,
-                                     T* __restrict__ z, int64_t n, int d) {
+__global__ void head_residual_kernel(const T* __restrict__ h, const float* __restrict__ pre, int n_part,
+                                     int64_t part_stride, const T* __restrict__ b1, T* __restrict__ z, int64_t n,
+                                     int d) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n) return;
-  float p = pre[idx] + (b1 ? to_float(b1[idx % d]) : 0.f);
+  float p = 0.f;
+  for (int s = 0; s < n_part; ++s) p += pre[(int64_t)s * part_stride + idx];
+  p += b1 ? to_float(b1[idx % d]) : 0.f;
   z[idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
 }
 
-int launch_head_residual(int dtype, const void* h, const float* pre, const void* b1, void* z, int B, int d,
+int launch_head_residual(int dtype, const void* h, const Partials& pre, const void* b1, void* z, int B, int d,
                          hipStream_t st) {
   ProfScope prof_(PROF_MISC, st);
   int64_t n = (int64_t)B * d;
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
   if (dtype == MDZ_BF16)
-    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre, (const bf16_t*)b1, (bf16_t*)z, n, d);
+    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre.p, pre.n, pre.stride, (const bf16_t*)b1,
+                                                         (bf16_t*)z, n, d);
   else
-    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre, (const float*)b1, (float*)z, n, d);
+    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre.p, pre.n, pre.stride, (const float*)b1,
+                                                        (float*)z, n, d);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

@@ -6,6 +6,15 @@
 
 namespace mdz {
 
+// Output of a GEMM: n partial sums, each [M][ld] fp32, `stride` elements apart; the consumer adds them in
+// the order 0..n-1 (fixed, so results do not depend on scheduling).
+struct Partials {
+  const float* p;
+  int n;
+  int64_t stride;
+  int64_t ld;
+};
+
 // ---- layout movers (layout.hip) ------------------------------------------------------------------
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, hipStream_t st);
@@ -18,23 +27,25 @@ int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, 
 // ---- elementwise / small kernels (elementwise.hip) -------------------------------------------------
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
                  hipStream_t st);
-// xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g, rounded to the storage dtype
-int launch_rmsnorm(int dtype, const float* x, const void* g, void* xn, int rows, int d, float eps,
-                   hipStream_t st);
+// x[r] += sum of partials (skipped if part.p == NULL); then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g rounded
+// to the storage dtype (skipped if xn == NULL)
+int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
+                            float eps, hipStream_t st);
 // cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32
 int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
                       float* cs, hipStream_t st);
-// rotates q and k of qkv [B*T][3d] fp32; q -> q_out [B*T][d] storage dtype; k,v -> cache slots S_b + n
-int launch_rope_kvwrite(int dtype, int tree, const float* qkv, const float* cs, void* q_out, const KvGeom& g,
+// rotates q and k of qkv [B*T][3d] fp32 (given as partials); q -> q_out [B*T][d] storage dtype; k,v -> cache
+// slots S_b + n
+int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* cs, void* q_out, const KvGeom& g,
                         void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
                         hipStream_t st);
 // u[m][f] = SiLU(gate) * up from the tile-interleaved gate/up GEMM output gu [M][2F] fp32
-int launch_swiglu(int dtype, const float* gu, void* u, int M, int F, hipStream_t st);
+int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStream_t st);
 // gathers row src_row[b] of hidden [B][Tsrc][d] into h [B][d] (same dtype)
 int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, int B, int Tsrc, int d, void* h,
                        hipStream_t st);
 // z = h + SiLU(pre + b1) -> storage dtype
-int launch_head_residual(int dtype, const void* h, const float* pre, const void* b1, void* z, int B, int d,
+int launch_head_residual(int dtype, const void* h, const Partials& pre, const void* b1, void* z, int B, int d,
                          hipStream_t st);
 // storage-dtype copy of fp32 rows (hidden_out)
 int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
@@ -52,9 +63,11 @@ int launch_accept(int tree, const int32_t* tree_tokens, const int32_t* node_argm
                   int32_t* best_path, int32_t* acc_nodes, int32_t* acc_tokens, int32_t* next_root,
                   int32_t* last_node, hipStream_t st);
 
-// ---- GEMM: Y[m][n] (+)= sum_k X[m][k] * W[n][k], W packed, X storage dtype [M][K], Y fp32 ---------
-int launch_gemm(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy,
-                bool accumulate, hipStream_t st);
+// ---- GEMM: sum_k X[m][k] * W[n][k], W packed, X storage dtype [M][K] ------------------------------
+// Writes at most max_split partial sums into `out` (partial s at out + s*M*ld, leading dimension ld) and
+// describes them in *res.  max_split == 1 yields the finished product in out.
+int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld,
+                int max_split, Partials* res, hipStream_t st);
 
 // ---- tree-masked attention --------------------------------------------------------------------------
 // q [B*T][d] storage dtype (rotated); att_out [B*T][d] storage dtype

@@ -22,10 +22,23 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
                              int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                              hipStream_t st);
 
-int launch_gemm(int dtype, const void* X, const void* Wp, float* Y, int M, int N, int K, int64_t ldy, bool accumulate,
-                hipStream_t st) {
-  return launch_gemm_generic(dtype, X, Wp, Y, M, N, K, ldy, accumulate, st);
+bool gemm_mfma_supported(int dtype, int M, int N, int K);
+int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
+                     int max_split, int* n_part, hipStream_t st);
+
+int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld, int max_split,
+                Partials* res, hipStream_t st) {
+  res->p = out;
+  res->n = 1;
+  res->stride = (int64_t)M * ld;
+  res->ld = ld;
+  if (gemm_mfma_supported(dtype, M, N, K))
+    return launch_gemm_mfma(X, Wp, out, M, N, K, ld, res->stride, max_split, &res->n, st);
+  return launch_gemm_generic(dtype, X, Wp, out, M, N, K, ld, false, st);
 }
+
+// split-K is only worth its partial-sum traffic for skinny problems
+static int max_split_for(int rows) { return rows <= 64 ? 8 : 1; }
 
 int64_t tree_attention_scratch_bytes(int, int, const KvGeom&, int, int) { return 0; }
 
@@ -37,7 +50,7 @@ int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, c
 
 // ---- workspace ------------------------------------------------------------------------------------
 struct Workspace {
-  int64_t rope_cs, x, xn, qkv, q, att, gu, u, logits, h, pre, z, hlogits, attn_scratch, total;
+  int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, attn_scratch, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~int64_t(255); }
@@ -56,14 +69,17 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.rope_cs = take(rows * (m.head_dim / 2) * 2 * 4);
   w.x = take(rows * m.d * 4);
   w.xn = take(rows * m.d * es);
-  w.qkv = take(rows * 3 * m.d * 4);
+  {
+    int64_t widest = 3 * (int64_t)m.d > 2 * (int64_t)m.ffn ? 3 * (int64_t)m.d : 2 * (int64_t)m.ffn;
+    int64_t layer_part = max_split_for((int)rows) * rows * widest * 4;
+    int64_t head_part = max_split_for(B) * (int64_t)B * m.d * 4;
+    w.part = take(layer_part > head_part ? layer_part : head_part);
+  }
   w.q = take(rows * m.d * es);
   w.att = take(rows * m.d * es);
-  w.gu = take(rows * 2 * m.ffn * 4);
   w.u = take(rows * m.ffn * es);
   w.logits = take(rows * (int64_t)m.vocab * 4);
   w.h = take((int64_t)B * m.d * es);
-  w.pre = take((int64_t)B * m.d * 4);
   w.z = take((int64_t)B * m.d * es);
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
   KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T};
@@ -108,33 +124,36 @@ static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int m
 
 static KvGeom geom(const mdz_kv_desc* kv) { return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap}; }
 
-// One decoder layer over rows = B*T rows of x.
+// One decoder layer over rows = B*T rows of x.  On entry ws.xn holds RMSNorm(x; g_attn of this layer).  The
+// layer's last residual update is fused with the NEXT norm: x += down-projection partials, then
+// xn_next = RMSNorm(x; g_next) is written to xn_next (NULL: residual update only).
 static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int layer, float* x, const mdz_kv_desc* kv,
-                     const int32_t* seq_len, int B, int max_prefix, char* ws, const Workspace& w, hipStream_t st) {
+                     const int32_t* seq_len, int B, int max_prefix, char* ws, const Workspace& w, const void* g_next,
+                     void* xn_next, hipStream_t st) {
   const TreeTables* t = host_tree(m.tree);
   const int rows = B * t->T;
+  const int ms = max_split_for(rows);
   const KvGeom g = geom(kv);
   int rc;
   float* cs = (float*)(ws + w.rope_cs);
   void* xn = ws + w.xn;
-  float* qkv = (float*)(ws + w.qkv);
+  float* part = (float*)(ws + w.part);
   void* q = ws + w.q;
   void* att = ws + w.att;
-  float* gu = (float*)(ws + w.gu);
   void* u = ws + w.u;
-  if ((rc = launch_rmsnorm(m.dtype, x, lw.g_attn, xn, rows, m.d, m.rms_eps, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, qkv, rows, 3 * m.d, m.d, 3 * m.d, false, st))) return rc;
-  if ((rc = launch_rope_kvwrite(m.dtype, m.tree, qkv, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, st)))
+  Partials pr;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, 3 * m.d, m.d, 3 * m.d, ms, &pr, st))) return rc;
+  if ((rc = launch_rope_kvwrite(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, st)))
     return rc;
   if ((rc = launch_tree_attention(m.dtype, m.tree, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
                                   ws + w.attn_scratch, w.total - w.attn_scratch, st)))
     return rc;
-  if ((rc = launch_gemm(m.dtype, att, lw.wo, x, rows, m.d, m.d, m.d, true, st))) return rc;
-  if ((rc = launch_rmsnorm(m.dtype, x, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, gu, rows, 2 * m.ffn, m.d, 2 * m.ffn, false, st))) return rc;
-  if ((rc = launch_swiglu(m.dtype, gu, u, rows, m.ffn, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, u, lw.wdown, x, rows, m.d, m.ffn, m.d, true, st))) return rc;
-  return MDZ_OK;
+  if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, &pr, st))) return rc;
+  if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
+  if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, &pr, st))) return rc;
+  return launch_residual_rmsnorm(m.dtype, x, pr, g_next, xn_next, rows, m.d, m.rms_eps, st);
 }
 
 static int check_layer_weights(const mdz_layer_weights* lw) {
@@ -260,8 +279,9 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   hipStream_t st = (hipStream_t)stream;
   char* wsb = (char*)ws;
   void* h = wsb + L.h;
-  float* pre = (float*)(wsb + L.pre);
+  float* part = (float*)(wsb + L.part);
   void* z = wsb + L.z;
+  Partials pr;
   const int64_t V = m.vocab;
   const int64_t ld = (int64_t)(t->K + 1) * V;  // row stride of the [B][K+1][V] logits
   float* hl = head_logits_opt ? head_logits_opt : (float*)(wsb + L.hlogits);
@@ -270,16 +290,16 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   if (root_token) {
     if ((rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
   } else {
-    if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, false, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, st))) return rc;
   }
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
     const void* b1 = w->head_b1 ? w->head_b1[k] : nullptr;
-    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], pre, B, m.d, m.d, m.d, false, st))) return rc;
-    if ((rc = launch_head_residual(m.dtype, h, pre, b1, z, B, m.d, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part, B, m.d, m.d, m.d, max_split_for(B), &pr, st))) return rc;
+    if ((rc = launch_head_residual(m.dtype, h, pr, b1, z, B, m.d, st))) return rc;
     float* lk = hl + (int64_t)(k + 1) * V;
-    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, false, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, st))) return rc;
     seg += t->caps[k];
   }
@@ -307,7 +327,11 @@ int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, 
   if ((rc = launch_rope_table(model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
                               (float*)((char*)ws + L.rope_cs), st)))
     return rc;
-  return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, st);
+  const int rows = B * t->T;
+  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, Partials{nullptr, 0, 0, 0}, lw->g_attn, (char*)ws + L.xn, rows,
+                                    model->d, model->rms_eps, st)))
+    return rc;
+  return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, nullptr, nullptr, st);
 }
 
 int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const int32_t* tree_tokens,
@@ -335,12 +359,20 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   if ((rc = launch_rope_table(m.tree, seq_len, B, max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs), st)))
     return rc;
   if ((rc = launch_embed(m.dtype, w->embed, tree_tokens, x, rows, m.d, m.vocab, st))) return rc;
-  for (int l = 0; l < m.n_layers; ++l)
-    if ((rc = run_layer(m, w->layers[l], l, x, kv, seq_len, B, max_prefix, wsb, L, st))) return rc;
-  void* hid = hidden_out ? hidden_out : (void*)(wsb + L.xn);
-  if ((rc = launch_rmsnorm(m.dtype, x, w->g_final, hid, rows, m.d, m.rms_eps, st))) return rc;
+  void* xn = wsb + L.xn;
+  void* hid = hidden_out ? hidden_out : xn;
+  if ((rc = launch_residual_rmsnorm(m.dtype, x, Partials{nullptr, 0, 0, 0}, w->layers[0].g_attn, xn, rows, m.d,
+                                    m.rms_eps, st)))
+    return rc;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const bool last = l + 1 == m.n_layers;
+    if ((rc = run_layer(m, w->layers[l], l, x, kv, seq_len, B, max_prefix, wsb, L,
+                        last ? w->g_final : w->layers[l + 1].g_attn, last ? hid : xn, st)))
+      return rc;
+  }
   float* logits = logits_opt ? logits_opt : (float*)(wsb + L.logits);
-  if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, false, st))) return rc;
+  Partials pr;
+  if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, 1, &pr, st))) return rc;
   return launch_argmax(logits, rows, m.vocab, m.vocab, node_argmax, st);
 }
 
