@@ -46,9 +46,8 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(int tree, const T* __
       bool vis = j < S || ((mask >> (j - S)) & 1ull);
       float s = -INFINITY;
       if (vis) {
-        const T* kr = kc + k_index(g, layer, b, h, j, 0);
         s = 0.f;
-        for (int e = 0; e < hd; ++e) s += qs[e] * to_float(kr[e]);
+        for (int e = 0; e < hd; ++e) s += qs[e] * to_float(kc[k_index(g, layer, b, h, j, e)]);
       }
       p[j - c0] = s;
       lm = fmaxf(lm, s);

@@ -1,0 +1,332 @@
+// Tree-masked attention for bf16 storage, 64-node tree, head_dim 128, on gfx950 MFMA
+// (Section 3.2: all T candidates attend in one pass; node i sees the whole prefix plus the tree slots
+// its row of the static visibility matrix allows).
+//
+// One workgroup = 4 waves handles one (sequence, head, key-split).  All 64 queries ride along every
+// key, so K and V are read from HBM exactly once per head.  A wave walks 32-key blocks of the tiled
+// cache (common.h): each 1 KiB unit is loaded with one contiguous 16-byte-per-lane load and used
+// directly as an MFMA A operand.  Scores are computed transposed (keys x queries), which leaves every
+// lane with 16 keys of ONE query: the running max / sum need a single exchange with lane+32, and the
+// probabilities are packed to bf16 in place as the B operand of the second MFMA (out^T = V^T P^T).
+// The tree mask is one 64-bit word per query (a compile-time table) tested only in blocks that reach
+// past the prefix.  Waves merge through LDS, key-splits through a small second kernel, both in a fixed
+// order, so results are deterministic.
+#include "kernels.h"
+
+namespace mdz {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHD = 128;         // head_dim
+constexpr int kTQ = 64;          // queries (tree nodes)
+constexpr int kOPad = kTQ + 1;   // LDS row stride of the merge buffer (floats)
+constexpr int kQRow = kHD * 2 + 16;  // bytes per staged Q row
+constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  // round to nearest even, finite non-negative inputs
+  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+  ua += 0x7FFFu + ((ua >> 16) & 1u);
+  ub += 0x7FFFu + ((ub >> 16) & 1u);
+  return (ua >> 16) | (ub & 0xFFFF0000u);
+}
+
+__global__ void __launch_bounds__(256)
+    attn_tree_mfma_kernel(int tree, const bf16_t* __restrict__ q, KvGeom g, const bf16_t* __restrict__ kc,
+                          const bf16_t* __restrict__ vc, int layer, const int32_t* __restrict__ seq_len,
+                          int max_prefix, bf16_t* __restrict__ att_out, float* __restrict__ part_o,
+                          float* __restrict__ part_ml) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const TreeTables& t = c_trees[tree];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qi = lane & 31, gh = lane >> 5;
+  const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y, b = blockIdx.z;
+  const int d = g.n_heads * kHD;
+  const int S = min(max(seq_len[b], 0), max_prefix);
+  const int n_slots = S + kTQ;
+  const int nb = (n_slots + 31) >> 5;
+  const int blk_begin = (int)((int64_t)split * nb / n_splits), blk_end = (int)((int64_t)(split + 1) * nb / n_splits);
+
+  // Q tile of this head -> LDS (rows padded by 16 B: the 16 B-per-lane operand reads below are bank-conflict
+  // free).  The region is reused by the wave merge after the key loop.
+  uint8_t* q_lds = reinterpret_cast<uint8_t*>(lds);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int idx = threadIdx.x + i * 256;
+    int row = idx >> 4, col = idx & 15;
+    *reinterpret_cast<u32x4*>(q_lds + row * kQRow + col * 16) =
+        *reinterpret_cast<const u32x4*>(q + (int64_t)(b * kTQ + row) * d + h * kHD + col * 8);
+  }
+  __syncthreads();
+  // B operand of scores^T: lane holds query 32u + qi, features 16ks + 8gh .. +7
+  const uint8_t* qfrag = q_lds + qi * kQRow + gh * 16;
+  const uint64_t mq[2] = {t.anc_mask[qi], t.anc_mask[32 + qi]};
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
+
+  const int64_t head_base = kv_head_base(g, layer, b, h);
+  const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
+  const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  f32x16 o[4][2];
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[tt][u][r] = 0.f;
+
+  // K is double buffered one block ahead; V of a block is requested when its scores start, so its
+  // latency hides behind the 16 score MFMAs and the softmax arithmetic (and the other waves of the CU).
+  u32x4 kb[2][8];
+  auto load_k = [&](int blk, u32x4 (&kd)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kd[i] = kp[(int64_t)blk * 512 + i * 64];
+  };
+  auto process = [&](int blk, const u32x4 (&kd)[8]) {
+    // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
+    // than in 64 registers per lane that this kernel does not have to spare.
+    asm volatile("" ::: "memory");
+    u32x4 vd[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vd[i] = vp[(int64_t)blk * 512 + i * 64];
+    f32x16 sc[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[u][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      bf16x8 a = __builtin_bit_cast(bf16x8, kd[ks]);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 qv = *reinterpret_cast<const bf16x8*>(qfrag + u * 32 * kQRow + ks * 32);
+        sc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qv, sc[u], 0, 0, 0);
+      }
+    }
+    // Visibility of this block's 32 keys for the lane's query, as one 32-bit word: prefix keys are
+    // visible, a tree key S+j is visible iff bit j of the query's ancestor mask is set, keys beyond the
+    // tree are not.  rel0 (wave-uniform) = offset of the block's first key from the tree's first slot.
+    const int rel0 = blk * 32 - S;
+    const bool need_mask = rel0 + 32 > 0;  // wave-uniform: the block reaches past the prefix
+    float alpha[2];
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      uint32_t vis = 0xFFFFFFFFu;
+      if (need_mask) {
+        uint32_t pre = rel0 >= 0 ? 0u : (0xFFFFFFFFu >> (32 + rel0));          // keys below S (rel0 in [-31,-1])
+        uint64_t tr = rel0 >= 0 ? (mq[u] >> rel0) : (mq[u] << (-rel0));        // rel0 in [-31, 63]
+        vis = (pre | (uint32_t)tr) >> (4 * gh);
+      }
+      float bmax = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float s = sc[u][r] * scale_log2;
+        s = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s : -INFINITY;
+        sc[u][r] = s;
+        bmax = fmaxf(bmax, s);
+      }
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+      float m_new = fmaxf(m_run[u], bmax);
+      float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      alpha[u] = fast_exp2(m_run[u] - m_safe);
+      float sum = 0.f;
+      uint32_t pk[8];
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        float p0 = fast_exp2(sc[u][r] - m_safe), p1 = fast_exp2(sc[u][r + 1] - m_safe);
+        sum += p0 + p1;
+        pk[r >> 1] = pack_bf16x2(p0, p1);
+      }
+      l_run[u] = l_run[u] * alpha[u] + sum;
+      m_run[u] = m_new;
+      pf[u][0] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
+      pf[u][1] = __builtin_bit_cast(bf16x8, u32x4{pk[4], pk[5], pk[6], pk[7]});
+    }
+    if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) {
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[tt][u][r] *= alpha[u];
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        bf16x8 a = __builtin_bit_cast(bf16x8, vd[tt * 2 + s2]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) o[tt][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[u][s2], o[tt][u], 0, 0, 0);
+      }
+  };
+
+  int blk = blk_begin + wave;
+  if (blk < blk_end) {
+    load_k(blk, kb[0]);
+    while (true) {
+      bool more = blk + 4 < blk_end;
+      if (more) load_k(blk + 4, kb[1]);
+      process(blk, kb[0]);
+      if (!more) break;
+      blk += 4;
+      more = blk + 4 < blk_end;
+      if (more) load_k(blk + 4, kb[0]);
+      process(blk, kb[1]);
+      if (!more) break;
+      blk += 4;
+    }
+  }
+
+  // ---- merge the four waves through LDS (fixed order) ------------------------------------------
+  __syncthreads();  // every wave is done reading the Q tile that the merge buffer overlays
+  float* o_lds = lds;                             // [4][kHD][kOPad]
+  float* m_lds = lds + 4 * kHD * kOPad;           // [4][kTQ]
+  float* l_lds = m_lds + 4 * kTQ;                 // [4][kTQ]
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+    if (gh == 0) {
+      m_lds[wave * kTQ + 32 * u + qi] = m_run[u];
+      l_lds[wave * kTQ + 32 * u + qi] = l_tot;
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int hd = 32 * tt + 8 * (r >> 2) + 4 * gh + (r & 3);
+        o_lds[(wave * kHD + hd) * kOPad + 32 * u + qi] = o[tt][u][r];
+      }
+  }
+  __syncthreads();
+  const int qq = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 32;
+  float mw[4], M = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    mw[w] = m_lds[w * kTQ + qq];
+    M = fmaxf(M, mw[w]);
+  }
+  const float M_safe = M == -INFINITY ? 0.f : M;
+  float L = 0.f, wt[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    wt[w] = fast_exp2(mw[w] - M_safe);
+    L += wt[w] * l_lds[w * kTQ + qq];
+  }
+  float acc[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    float a = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) a += wt[w] * o_lds[(w * kHD + seg + j) * kOPad + qq];
+    acc[j] = a;
+  }
+  if (n_splits == 1) {
+    const float inv = 1.0f / L;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + seg);
+#pragma unroll
+    for (int j = 0; j < 32; j += 2) {
+      bf16_t lo = float_to_bf16(acc[j] * inv), hi = float_to_bf16(acc[j + 1] * inv);
+      dst[j >> 1] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
+    }
+  } else {
+    const int64_t pidx = ((int64_t)(b * g.n_heads + h) * n_splits + split);
+    float* po = part_o + (pidx * kTQ + qq) * kHD + seg;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) po[j] = acc[j];
+    if ((threadIdx.x & 3) == 0) {
+      part_ml[(pidx * 2 + 0) * kTQ + qq] = M;
+      part_ml[(pidx * 2 + 1) * kTQ + qq] = L;
+    }
+  }
+}
+
+// Merges the key-splits of one (sequence, head): fixed order, exact same weighting rule as above.
+__global__ void __launch_bounds__(256)
+    attn_combine_kernel(int n_heads, int n_splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                        bf16_t* __restrict__ att_out) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int d = n_heads * kHD;
+  const int qq = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 32;
+  const int64_t p0 = (int64_t)(b * n_heads + h) * n_splits;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((p0 + s) * 2 + 0) * kTQ + qq]);
+  float L = 0.f;
+  float acc[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) acc[j] = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
+    L += w * part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
+    const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + seg);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float4 v = po[j];
+      acc[4 * j] += w * v.x;
+      acc[4 * j + 1] += w * v.y;
+      acc[4 * j + 2] += w * v.z;
+      acc[4 * j + 3] += w * v.w;
+    }
+  }
+  const float inv = 1.0f / L;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + seg);
+#pragma unroll
+  for (int j = 0; j < 32; j += 2) {
+    bf16_t lo = float_to_bf16(acc[j] * inv), hi = float_to_bf16(acc[j + 1] * inv);
+    dst[j >> 1] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
+  }
+}
+
+bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
+  return dtype == MDZ_BF16 && g.tiled && g.head_dim == kHD && host_tree(tree)->T == kTQ;
+}
+
+static int attn_splits(int B, int n_heads, int max_prefix) {
+  int nb = (max_prefix + kTQ + 31) / 32;
+  int by_len = nb / 8;                               // >= 2 blocks per wave
+  int by_fill = (512 + B * n_heads - 1) / (B * n_heads);  // aim at ~512 workgroups
+  int s = by_len < by_fill ? by_len : by_fill;
+  if (s > 32) s = 32;
+  if (s < 1) s = 1;
+  return s;
+}
+
+int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
+  int s = attn_splits(B, n_heads, max_prefix);
+  return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
+}
+
+int launch_attention_mfma(int tree, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                          const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                          int64_t scratch_bytes, hipStream_t st) {
+  ProfScope prof_(PROF_ATTN, st);
+  if (B == 0) return MDZ_OK;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
+    attr_set = true;
+  }
+  const int splits = attn_splits(B, g.n_heads, max_prefix);
+  MDZ_REQUIRE(scratch_bytes >= attn_mfma_scratch_bytes(B, g.n_heads, max_prefix), MDZ_EWORKSPACE,
+              "attention: scratch too small");
+  float* part_o = (float*)scratch;
+  float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kTQ * kHD;
+  dim3 grid(splits, g.n_heads, B);
+  attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, g, (const bf16_t*)kc,
+                                                          (const bf16_t*)vc, layer, seq_len, max_prefix,
+                                                          (bf16_t*)att_out, part_o, part_ml);
+  MDZ_LAUNCH_CHECK();
+  if (splits > 1) {
+    attn_combine_kernel<<<dim3(g.n_heads, B), 256, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
+    MDZ_LAUNCH_CHECK();
+  }
+  return MDZ_OK;
+}
+
+}  // namespace mdz

@@ -100,18 +100,41 @@ struct Packed<float> {
 
 // ---- KV cache layout ---------------------------------------------------------------------------
 // The library owns this layout; callers go through medusa_kv_write / medusa_kv_read.
+// fp32: plain [layer][seq][head][slot][feature] for K and V.
+// bf16: per (layer, seq, head) the slots are grouped in blocks of 32; a block is a sequence of 1 KiB
+// units of 64 lanes x 8 bf16, each unit being one MFMA A operand of the attention kernel, so a wave
+// streams K and V with contiguous 16-byte-per-lane loads and no transposition:
+//   K block (scores^T = K Q^T, rows = keys, contraction over features): unit ks holds for lane l
+//     key (l % 32), features 16*ks + 8*(l / 32) .. +7.
+//   V block (out^T = V^T P^T, rows = features, contraction over keys): unit (2*t + s2) holds for lane l
+//     feature 32*t + (l % 32) and the 8 keys 16*s2 + 8*(e / 4) + 4*(l / 32) + (e % 4), e = 0..7 — the
+//     order in which the score MFMA leaves its 16 keys per lane, so probabilities feed the second MFMA
+//     straight from registers.
 struct KvGeom {
   int n_layers, batch, n_heads, head_dim, cap;
+  int tiled;  // 1: bf16 block layout above (head_dim % 32 == 0); 0: plain
 };
+__host__ __device__ inline int kv_cap_pad(const KvGeom& g) { return g.tiled ? (g.cap + 31) & ~31 : g.cap; }
+__host__ __device__ inline int64_t kv_head_base(const KvGeom& g, int l, int b, int h) {
+  return (((int64_t)l * g.batch + b) * g.n_heads + h) * (int64_t)kv_cap_pad(g) * g.head_dim;
+}
 // K element (layer l, sequence b, head h, slot pos, feature i)
 __host__ __device__ inline int64_t k_index(const KvGeom& g, int l, int b, int h, int pos, int i) {
-  return ((((int64_t)l * g.batch + b) * g.n_heads + h) * g.cap + pos) * g.head_dim + i;
+  int64_t base = kv_head_base(g, l, b, h);
+  if (!g.tiled) return base + (int64_t)pos * g.head_dim + i;
+  int blk = pos >> 5, key = pos & 31, ks = i >> 4, kh = (i >> 3) & 1, e = i & 7;
+  return base + (int64_t)blk * 32 * g.head_dim + ks * 512 + (key + 32 * kh) * 8 + e;
 }
 __host__ __device__ inline int64_t v_index(const KvGeom& g, int l, int b, int h, int pos, int i) {
-  return ((((int64_t)l * g.batch + b) * g.n_heads + h) * g.cap + pos) * g.head_dim + i;
+  int64_t base = kv_head_base(g, l, b, h);
+  if (!g.tiled) return base + (int64_t)pos * g.head_dim + i;
+  int blk = pos >> 5, kk = pos & 31;
+  int s2 = kk >> 4, ehi = (kk >> 3) & 1, kh = (kk >> 2) & 1, elo = kk & 3;
+  int t = i >> 5, row = i & 31;
+  return base + (int64_t)blk * 32 * g.head_dim + (t * 2 + s2) * 512 + (row + 32 * kh) * 8 + (ehi * 4 + elo);
 }
 inline int64_t kv_elems(const KvGeom& g) {
-  return (int64_t)g.n_layers * g.batch * g.n_heads * g.cap * g.head_dim;
+  return (int64_t)g.n_layers * g.batch * g.n_heads * kv_cap_pad(g) * g.head_dim;
 }
 
 // ---- device copies of the trees -----------------------------------------------------------------

@@ -40,11 +40,22 @@ int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int
 // split-K is only worth its partial-sum traffic for skinny problems
 static int max_split_for(int rows) { return rows <= 64 ? 8 : 1; }
 
-int64_t tree_attention_scratch_bytes(int, int, const KvGeom&, int, int) { return 0; }
+bool attn_mfma_supported(int dtype, int tree, const KvGeom& g);
+int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix);
+int launch_attention_mfma(int tree, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                          const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                          int64_t scratch_bytes, hipStream_t st);
+
+int64_t tree_attention_scratch_bytes(int dtype, int tree, const KvGeom& g, int B, int max_prefix) {
+  return attn_mfma_supported(dtype, tree, g) ? attn_mfma_scratch_bytes(B, g.n_heads, max_prefix) : 0;
+}
 
 int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
-                          int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void*, int64_t,
-                          hipStream_t st) {
+                          int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                          int64_t scratch_bytes, hipStream_t st) {
+  if (attn_mfma_supported(dtype, tree, g))
+    return launch_attention_mfma(tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch, scratch_bytes,
+                                 st);
   return launch_attention_generic(dtype, tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, st);
 }
 
@@ -82,7 +93,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.h = take((int64_t)B * m.d * es);
   w.z = take((int64_t)B * m.d * es);
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
-  KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T};
+  KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T, (m.dtype == MDZ_BF16 && m.head_dim % 32 == 0) ? 1 : 0};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
   w.total = off;
   return w;
@@ -122,7 +133,10 @@ static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int m
   return MDZ_OK;
 }
 
-static KvGeom geom(const mdz_kv_desc* kv) { return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap}; }
+static KvGeom geom(const mdz_kv_desc* kv) {
+  return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap,
+                (kv->dtype == MDZ_BF16 && kv->head_dim % 32 == 0) ? 1 : 0};
+}
 
 // One decoder layer over rows = B*T rows of x.  On entry ws.xn holds RMSNorm(x; g_attn of this layer).  The
 // layer's last residual update is fused with the NEXT norm: x += down-projection partials, then
