@@ -68,16 +68,59 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
   for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
 }
 
+// Fast path for d == 4 * blockDim (d = 4096 with 1024 threads): every thread owns one float4 of the row, all
+// partial loads are issued at once, and the row never leaves registers between the two halves.
+template <typename T>
+__global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __restrict__ x, const float* __restrict__ P,
+                                                                     int n_part, int64_t part_stride, int64_t ldp,
+                                                                     const T* __restrict__ g, T* __restrict__ xn,
+                                                                     int d, float eps) {
+  __shared__ float red[16];
+  const int r = blockIdx.x, i = threadIdx.x * 4;
+  float4 v = *reinterpret_cast<const float4*>(x + (int64_t)r * d + i);
+  if (P) {
+    for (int s = 0; s < n_part; ++s) {
+      float4 p = *reinterpret_cast<const float4*>(P + (int64_t)s * part_stride + (int64_t)r * ldp + i);
+      v.x += p.x;
+      v.y += p.y;
+      v.z += p.z;
+      v.w += p.w;
+    }
+    *reinterpret_cast<float4*>(x + (int64_t)r * d + i) = v;
+  }
+  if (!xn) return;
+  float ss = wave_sum(v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += red[w];
+  const float rs = 1.0f / sqrtf(tot / (float)d + eps);
+  T o[4] = {from_float<T>(v.x * rs * to_float(g[i])), from_float<T>(v.y * rs * to_float(g[i + 1])),
+            from_float<T>(v.z * rs * to_float(g[i + 2])), from_float<T>(v.w * rs * to_float(g[i + 3]))};
+  T* dst = xn + (int64_t)r * d + i;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dst[j] = o[j];
+}
+
 int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
                             float eps, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
-  if (dtype == MDZ_BF16)
+  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0) {
+    if (dtype == MDZ_BF16)
+      residual_rmsnorm_vec4_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, part.p, part.n, part.stride, part.ld,
+                                                                  (const bf16_t*)g, (bf16_t*)xn, d, eps);
+    else
+      residual_rmsnorm_vec4_kernel<float><<<rows, 1024, 0, st>>>(x, part.p, part.n, part.stride, part.ld,
+                                                                 (const float*)g, (float*)xn, d, eps);
+  } else if (dtype == MDZ_BF16) {
     residual_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const bf16_t*)g,
                                                           (bf16_t*)xn, d, eps);
-  else
+  } else {
     residual_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const float*)g,
                                                          (float*)xn, d, eps);
+  }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

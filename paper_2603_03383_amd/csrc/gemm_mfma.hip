@@ -62,9 +62,10 @@ __global__ void __launch_bounds__(WPB * 64)
     for (int i = 0; i < XL; ++i) {
       int idx = threadIdx.x + i * (WPB * 64);
       int row = idx >> 4, col = idx & 15;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (row < M) v = *reinterpret_cast<const u32x4*>(X + (int64_t)row * K + (int64_t)c * kChunkK + col * 8);
-      xr[i] = v;
+      // branch-free and wait-free: tile rows beyond M re-read row M-1.  An output row depends only on its own
+      // X row, and rows >= M are never stored, so their contents do not matter.
+      int rr = row < M ? row : M - 1;
+      xr[i] = *reinterpret_cast<const u32x4*>(X + (int64_t)rr * K + (int64_t)c * kChunkK + col * 8);
     }
   };
   auto store_x = [&](int buf) {
@@ -80,7 +81,7 @@ __global__ void __launch_bounds__(WPB * 64)
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int ks = 0; ks < kChunkSteps; ++ks)
-        dst[nt][ks] = live[nt] ? wp[nt][((int64_t)c * kChunkSteps + ks) * 64] : u32x4{0u, 0u, 0u, 0u};
+        dst[nt][ks] = wp[nt][((int64_t)c * kChunkSteps + ks) * 64];  // dead tiles alias tile 0; never stored
   };
   auto compute = [&](int buf, const u32x4 (&w)[NT][kChunkSteps]) {
     const uint8_t* base = &lds[buf][(lane & 31) * kLdsRow + (lane >> 5) * 16];
@@ -106,29 +107,36 @@ __global__ void __launch_bounds__(WPB * 64)
     store_x(0);
     __syncthreads();
     int c = c_begin;
-    while (true) {
-      // stage A: compute buffer 0, prefetch into buffer 1
-      bool more = c + 1 < c_end;
-      if (more) {
-        load_x(c + 1);
-        load_w(c + 1, wb[1]);
-      }
+    // steady state: two chunks per trip, no branches inside, so the prefetch of chunk c+1 stays in flight
+    // while chunk c is multiplied
+    // sched_barrier: the loads must be ISSUED before the MFMAs of the previous chunk, not sunk below them
+    for (; c + 2 < c_end; c += 2) {
+      load_x(c + 1);
+      load_w(c + 1, wb[1]);
+      __builtin_amdgcn_sched_barrier(0);
       compute(0, wb[0]);
-      if (!more) break;
+      __builtin_amdgcn_sched_barrier(0);
       store_x(1);
       __syncthreads();
-      ++c;
-      // stage B: compute buffer 1, prefetch into buffer 0
-      more = c + 1 < c_end;
-      if (more) {
-        load_x(c + 1);
-        load_w(c + 1, wb[0]);
-      }
+      load_x(c + 2);
+      load_w(c + 2, wb[0]);
+      __builtin_amdgcn_sched_barrier(0);
       compute(1, wb[1]);
-      if (!more) break;
+      __builtin_amdgcn_sched_barrier(0);
       store_x(0);
       __syncthreads();
-      ++c;
+    }
+    if (c + 1 < c_end) {  // two chunks left
+      load_x(c + 1);
+      load_w(c + 1, wb[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(0, wb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      store_x(1);
+      __syncthreads();
+      compute(1, wb[1]);
+    } else {  // one chunk left
+      compute(0, wb[0]);
     }
   }
 

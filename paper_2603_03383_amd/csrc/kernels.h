@@ -52,10 +52,13 @@ int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStre
 
 // ---- selection kernels (select.hip) -----------------------------------------------------------------
 // out[r] = argmax_v logits[r][v], ties -> lowest v
-int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, hipStream_t st);
+// (scratch: topk_scratch_bytes(rows, k) bytes enable the two-stage kernels for long rows; may be NULL)
+int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,
+                  hipStream_t st);
+int64_t topk_scratch_bytes(int rows, int k);
 // out[r][0..k) = indices of the k largest of logits[r][:], descending, ties -> lower index
-int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld,
-                hipStream_t st);
+int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld, void* scratch,
+                int64_t scratch_bytes, hipStream_t st);
 // dst[i * dst_stride] = src[i]
 int launch_scatter_i32(const int32_t* src, int32_t* dst, int n, int64_t dst_stride, hipStream_t st);
 int launch_tree_tokens(int tree, const int32_t* cand_flat, int32_t* tree_tokens, int B, hipStream_t st);

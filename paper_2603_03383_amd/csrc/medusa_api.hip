@@ -61,7 +61,7 @@ int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, c
 
 // ---- workspace ------------------------------------------------------------------------------------
 struct Workspace {
-  int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, attn_scratch, total;
+  int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, sel, sel_bytes, attn_scratch, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~int64_t(255); }
@@ -93,6 +93,8 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.h = take((int64_t)B * m.d * es);
   w.z = take((int64_t)B * m.d * es);
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
+  w.sel_bytes = topk_scratch_bytes((int)rows > B ? (int)rows : B, 16);
+  w.sel = take(w.sel_bytes);
   KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T, (m.dtype == MDZ_BF16 && m.head_dim % 32 == 0) ? 1 : 0};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
   w.total = off;
@@ -305,7 +307,7 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
     if ((rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
   } else {
     if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
-    if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, st))) return rc;
+    if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, wsb + L.sel, L.sel_bytes, st))) return rc;
   }
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
@@ -314,7 +316,8 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
     if ((rc = launch_head_residual(m.dtype, h, pr, b1, z, B, m.d, st))) return rc;
     float* lk = hl + (int64_t)(k + 1) * V;
     if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
-    if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, st))) return rc;
+    if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, wsb + L.sel, L.sel_bytes, st)))
+      return rc;
     seg += t->caps[k];
   }
   return launch_tree_tokens(m.tree, cand_flat, tree_tokens, B, st);
@@ -387,7 +390,7 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   float* logits = logits_opt ? logits_opt : (float*)(wsb + L.logits);
   Partials pr;
   if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, 1, &pr, st))) return rc;
-  return launch_argmax(logits, rows, m.vocab, m.vocab, node_argmax, st);
+  return launch_argmax(logits, rows, m.vocab, m.vocab, node_argmax, wsb + L.sel, L.sel_bytes, st);
 }
 
 int accept_longest_prefix(int tree, const int32_t* tree_tokens, const int32_t* node_argmax, int B,

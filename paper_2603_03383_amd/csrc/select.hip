@@ -66,17 +66,100 @@ __global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ log
   }
 }
 
-int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld,
-                hipStream_t st) {
+// ---- two-stage variant for long rows: stage 1 finds the top-k of each of kSelChunks column chunks (elements
+// held in registers), stage 2 merges the kSelChunks*k candidates.  The top-k of the union of per-chunk top-k
+// lists is the global top-k, and the order is total, so the result equals the single-stage kernel's.
+constexpr int kSelChunks = 64;
+constexpr int kSelPerThread = 8;  // stage 1 covers chunks of up to 256*8 = 2048 columns
+
+__global__ void __launch_bounds__(256) topk_stage1_kernel(const float* __restrict__ logits, int V, int64_t ld, int k,
+                                                          float* __restrict__ cand_v, int32_t* __restrict__ cand_i) {
+  __shared__ Best red[4];
+  const int chunk = blockIdx.x, row = blockIdx.y;
+  const int per = (V + kSelChunks - 1) / kSelChunks;
+  const int c0 = chunk * per, c1 = min(c0 + per, V);
+  const float* src = logits + (int64_t)row * ld;
+  float v[kSelPerThread];
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    int i = c0 + threadIdx.x + j * 256;
+    v[j] = i < c1 ? src[i] : -INFINITY;
+  }
+  float pv = INFINITY;
+  int pi = -1;
+  for (int p = 0; p < k; ++p) {
+    Best b{-INFINITY, kNoIndex};
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+      int i = c0 + threadIdx.x + j * 256;
+      bool ok = i < c1 && (p == 0 || precedes(pv, pi, v[j], i));
+      if (ok && precedes(v[j], i, b.v, b.i)) {
+        b.v = v[j];
+        b.i = i;
+      }
+    }
+    b = block_best_256(b, red);
+    if (threadIdx.x == 0) {
+      int64_t o = ((int64_t)row * kSelChunks + chunk) * k + p;
+      cand_v[o] = b.v;
+      cand_i[o] = b.i;
+    }
+    pv = b.v;
+    pi = b.i;
+  }
+}
+
+__global__ void __launch_bounds__(256) topk_stage2_kernel(const float* __restrict__ cand_v,
+                                                          const int32_t* __restrict__ cand_i, int k,
+                                                          int32_t* __restrict__ out, int64_t out_ld) {
+  __shared__ Best red[4];
+  const int row = blockIdx.x;
+  const int n = kSelChunks * k;  // <= 640 candidates
+  const float* cv = cand_v + (int64_t)row * n;
+  const int32_t* ci = cand_i + (int64_t)row * n;
+  float pv = INFINITY;
+  int pi = -1;
+  for (int p = 0; p < k; ++p) {
+    Best b{-INFINITY, kNoIndex};
+    for (int j = threadIdx.x; j < n; j += 256) {
+      float v = cv[j];
+      int i = ci[j];
+      bool ok = i != kNoIndex && (p == 0 || precedes(pv, pi, v, i));
+      if (ok && precedes(v, i, b.v, b.i)) {
+        b.v = v;
+        b.i = i;
+      }
+    }
+    b = block_best_256(b, red);
+    if (threadIdx.x == 0) out[(int64_t)row * out_ld + p] = b.i == kNoIndex ? -1 : b.i;
+    pv = b.v;
+    pi = b.i;
+  }
+}
+
+int64_t topk_scratch_bytes(int rows, int k) { return (int64_t)rows * kSelChunks * k * 8; }
+
+int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld, void* scratch,
+                int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_SELECT, st);
   if (rows == 0 || k == 0) return MDZ_OK;
-  topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
+  const int per = (V + kSelChunks - 1) / kSelChunks;
+  if (V >= 8192 && per <= 256 * kSelPerThread && scratch && scratch_bytes >= topk_scratch_bytes(rows, k)) {
+    float* cv = (float*)scratch;
+    int32_t* ci = (int32_t*)(cv + (int64_t)rows * kSelChunks * k);
+    topk_stage1_kernel<<<dim3(kSelChunks, rows), 256, 0, st>>>(logits, V, ld, k, cv, ci);
+    MDZ_LAUNCH_CHECK();
+    topk_stage2_kernel<<<rows, 256, 0, st>>>(cv, ci, k, out, out_ld);
+  } else {
+    topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
+  }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
 
-int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, hipStream_t st) {
-  return launch_topk(logits, rows, V, ld, 1, out, 1, st);
+int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,
+                  hipStream_t st) {
+  return launch_topk(logits, rows, V, ld, 1, out, 1, scratch, scratch_bytes, st);
 }
 
 __global__ void scatter_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int n,
