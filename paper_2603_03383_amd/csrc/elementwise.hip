@@ -46,10 +46,11 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
 // x[r] += sum_s P[s][r] (fixed order s = 0..n_part-1), then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g.
 // Either half is optional: P == nullptr skips the residual update, xn == nullptr skips the norm.
 template <typename T>
-__global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ P,
-                                                               int n_part, int64_t part_stride, int64_t ldp,
+__global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict__ x, Partials part,
                                                                const T* __restrict__ g, T* __restrict__ xn, int d,
                                                                float eps) {
+  const float* P = part.p;
+  const int64_t part_stride = part.stride, ldp = part.ld;
   __shared__ float red[4];
   int r = blockIdx.x;
   float* xr = x + (int64_t)r * d;
@@ -57,6 +58,7 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
   for (int i = threadIdx.x; i < d; i += 256) {
     float v = xr[i];
     if (P) {
+      const int n_part = part.count(i);
       for (int s = 0; s < n_part; ++s) v += P[(int64_t)s * part_stride + (int64_t)r * ldp + i];
       xr[i] = v;
     }
@@ -71,14 +73,16 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
 // Fast path for d == 4 * blockDim (d = 4096 with 1024 threads): every thread owns one float4 of the row, all
 // partial loads are issued at once, and the row never leaves registers between the two halves.
 template <typename T>
-__global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __restrict__ x, const float* __restrict__ P,
-                                                                     int n_part, int64_t part_stride, int64_t ldp,
+__global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __restrict__ x, Partials part,
                                                                      const T* __restrict__ g, T* __restrict__ xn,
                                                                      int d, float eps) {
+  const float* P = part.p;
+  const int64_t part_stride = part.stride, ldp = part.ld;
   __shared__ float red[16];
   const int r = blockIdx.x, i = threadIdx.x * 4;
   float4 v = *reinterpret_cast<const float4*>(x + (int64_t)r * d + i);
   if (P) {
+    const int n_part = part.count(i);  // band widths are multiples of 32, so one count covers the float4
     for (int s = 0; s < n_part; ++s) {
       float4 p = *reinterpret_cast<const float4*>(P + (int64_t)s * part_stride + (int64_t)r * ldp + i);
       v.x += p.x;
@@ -109,17 +113,13 @@ int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const voi
   if (rows == 0) return MDZ_OK;
   if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0) {
     if (dtype == MDZ_BF16)
-      residual_rmsnorm_vec4_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, part.p, part.n, part.stride, part.ld,
-                                                                  (const bf16_t*)g, (bf16_t*)xn, d, eps);
+      residual_rmsnorm_vec4_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, part, (const bf16_t*)g, (bf16_t*)xn, d, eps);
     else
-      residual_rmsnorm_vec4_kernel<float><<<rows, 1024, 0, st>>>(x, part.p, part.n, part.stride, part.ld,
-                                                                 (const float*)g, (float*)xn, d, eps);
+      residual_rmsnorm_vec4_kernel<float><<<rows, 1024, 0, st>>>(x, part, (const float*)g, (float*)xn, d, eps);
   } else if (dtype == MDZ_BF16) {
-    residual_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const bf16_t*)g,
-                                                          (bf16_t*)xn, d, eps);
+    residual_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, (const bf16_t*)g, (bf16_t*)xn, d, eps);
   } else {
-    residual_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part.p, part.n, part.stride, part.ld, (const float*)g,
-                                                         (float*)xn, d, eps);
+    residual_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, (const float*)g, (float*)xn, d, eps);
   }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
@@ -156,8 +156,7 @@ int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, i
 
 // grid (B*T, n_heads), block = head_dim/2 threads... generalised: threads stride over i < half.
 template <typename T>
-__global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, int n_part, int64_t part_stride,
-                                    const float* __restrict__ cs,
+__global__ void rope_kvwrite_kernel(int tree, Partials part, const float* __restrict__ cs,
                                     T* __restrict__ q_out, KvGeom g, T* __restrict__ kc, T* __restrict__ vc, int layer,
                                     const int32_t* __restrict__ seq_len, int max_prefix) {
   const TreeTables& t = c_trees[tree];
@@ -167,10 +166,12 @@ __global__ void rope_kvwrite_kernel(int tree, const float* __restrict__ qkv, int
   int hd = g.head_dim, half = hd / 2, d = g.n_heads * hd;
   int S = min(max(seq_len[b], 0), max_prefix);
   int slot = S + n;
-  const float* qr = qkv + (int64_t)row * 3 * d + h * hd;
-  auto rd = [&](int col) {  // fixed-order sum of the split-K partials
+  const float* qr = part.p + (int64_t)row * 3 * d;
+  auto rd = [&](int c) {  // fixed-order sum of the partial-sum slots of column h*hd + c
+    const int col = h * hd + c;
+    const int n_part = part.count(col);
     float v = 0.f;
-    for (int p = 0; p < n_part; ++p) v += qr[(int64_t)p * part_stride + col];
+    for (int p = 0; p < n_part; ++p) v += qr[(int64_t)p * part.stride + col];
     return v;
   };
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
@@ -196,10 +197,10 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   dim3 grid(B * t->T, g.n_heads);
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
   if (dtype == MDZ_BF16)
-    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv.p, qkv.n, qkv.stride, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
+    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
                                                           layer, seq_len, max_prefix);
   else
-    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv.p, qkv.n, qkv.stride, cs, (float*)q_out, g, (float*)kc, (float*)vc,
+    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv, cs, (float*)q_out, g, (float*)kc, (float*)vc,
                                                          layer, seq_len, max_prefix);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
@@ -209,8 +210,8 @@ __device__ inline float silu_f(float v) { return v / (1.0f + expf(-v)); }
 
 // gate feature f sits at column (2*(f/R))*R + f%R of gu, up at (2*(f/R)+1)*R + f%R (R = tile rows)
 template <typename T>
-__global__ void swiglu_kernel(const float* __restrict__ gu, int n_part, int64_t part_stride, T* __restrict__ u, int M,
-                              int F) {
+__global__ void swiglu_kernel(Partials part, T* __restrict__ u, int M, int F) {
+  const float* gu = part.p;
   constexpr int R = Packed<T>::kTileRows;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)M * F) return;
@@ -218,10 +219,9 @@ __global__ void swiglu_kernel(const float* __restrict__ gu, int n_part, int64_t 
   int64_t m = idx / F;
   int64_t col = (int64_t)(2 * (f / R)) * R + f % R;
   float gv = 0.f, uv = 0.f;
-  for (int p = 0; p < n_part; ++p) {
-    gv += gu[(int64_t)p * part_stride + m * 2 * F + col];
-    uv += gu[(int64_t)p * part_stride + m * 2 * F + col + R];
-  }
+  const int ng = part.count((int)col), nu = part.count((int)col + R);
+  for (int p = 0; p < ng; ++p) gv += gu[(int64_t)p * part.stride + m * 2 * F + col];
+  for (int p = 0; p < nu; ++p) uv += gu[(int64_t)p * part.stride + m * 2 * F + col + R];
   u[idx] = from_float<T>(silu_f(gv) * uv);
 }
 
@@ -231,9 +231,9 @@ int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStrea
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
   if (dtype == MDZ_BF16)
-    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu.p, gu.n, gu.stride, (bf16_t*)u, M, F);
+    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);
   else
-    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu.p, gu.n, gu.stride, (float*)u, M, F);
+    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu, (float*)u, M, F);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -260,13 +260,13 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
 }
 
 template <typename T>
-__global__ void head_residual_kernel(const T* __restrict__ h, const float* __restrict__ pre, int n_part,
-                                     int64_t part_stride, const T* __restrict__ b1, T* __restrict__ z, int64_t n,
-                                     int d) {
+__global__ void head_residual_kernel(const T* __restrict__ h, Partials part, const T* __restrict__ b1,
+                                     T* __restrict__ z, int64_t n, int d) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n) return;
   float p = 0.f;
-  for (int s = 0; s < n_part; ++s) p += pre[(int64_t)s * part_stride + idx];
+  const int n_part = part.count((int)(idx % d));
+  for (int s = 0; s < n_part; ++s) p += part.p[(int64_t)s * part.stride + idx];
   p += b1 ? to_float(b1[idx % d]) : 0.f;
   z[idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
 }
@@ -278,11 +278,9 @@ int launch_head_residual(int dtype, const void* h, const Partials& pre, const vo
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
   if (dtype == MDZ_BF16)
-    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre.p, pre.n, pre.stride, (const bf16_t*)b1,
-                                                         (bf16_t*)z, n, d);
+    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre, (const bf16_t*)b1, (bf16_t*)z, n, d);
   else
-    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre.p, pre.n, pre.stride, (const float*)b1,
-                                                        (float*)z, n, d);
+    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre, (const float*)b1, (float*)z, n, d);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

@@ -6,13 +6,17 @@
 
 namespace mdz {
 
-// Output of a GEMM: n partial sums, each [M][ld] fp32, `stride` elements apart; the consumer adds them in
-// the order 0..n-1 (fixed, so results do not depend on scheduling).
+// Output of a GEMM: partial-sum slots, each [M][ld] fp32, `stride` elements apart.  The consumer adds slots
+// 0..count-1 in that fixed order (results do not depend on scheduling); count is `n` for every column when
+// counts == NULL, else counts[column / band_cols].
 struct Partials {
   const float* p;
   int n;
   int64_t stride;
   int64_t ld;
+  const int32_t* counts;
+  int band_cols;
+  __host__ __device__ inline int count(int col) const { return counts ? counts[col / band_cols] : n; }
 };
 
 // ---- layout movers (layout.hip) ------------------------------------------------------------------
@@ -69,8 +73,9 @@ int launch_accept(int tree, const int32_t* tree_tokens, const int32_t* node_argm
 // ---- GEMM: sum_k X[m][k] * W[n][k], W packed, X storage dtype [M][K] ------------------------------
 // Writes at most max_split partial sums into `out` (partial s at out + s*M*ld, leading dimension ld) and
 // describes them in *res.  max_split == 1 yields the finished product in out.
+// counts: device scratch of N/32 + 1 ints that receives per-band slot counts when max_split > 1.
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld,
-                int max_split, Partials* res, hipStream_t st);
+                int max_split, int32_t* counts, Partials* res, hipStream_t st);
 
 // ---- tree-masked attention --------------------------------------------------------------------------
 // q [B*T][d] storage dtype (rotated); att_out [B*T][d] storage dtype
