@@ -35,11 +35,63 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return (ua >> 16) | (ub & 0xFFFF0000u);
 }
 
+__device__ inline u32x4 pack_bf16x8(const float* v) {
+  return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+}
+
+// One head-matrix (q, k or v of head h) of the QKV GEMM output for the prologue below: thread (row = t/4,
+// seg = t%4) sums the partial-sum slots (in order) of features [16*seg, 16*seg+16) and their rotary partners
+// [64 + 16*seg, ...): lo[16], hi[16].  Slots are fetched two at a time (16 float4 in flight per thread).
+__device__ inline void qkv_gather(const Partials& part, int64_t row, int col0, int seg, float (&lo)[16], float (&hi)[16]) {
+  const int n_part = part.count(col0);
+  const float* src = part.p + row * part.ld + col0 + 16 * seg;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) lo[i] = hi[i] = 0.f;
+  for (int p0 = 0; p0 < n_part; p0 += 2) {
+    float4 a[2][4], b[2][4];
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      if (p0 + k < n_part) {
+        const float* sp = src + (int64_t)(p0 + k) * part.stride;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[k][i] = *reinterpret_cast<const float4*>(sp + 4 * i);
+          b[k][i] = *reinterpret_cast<const float4*>(sp + 64 + 4 * i);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      if (p0 + k < n_part) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          lo[4 * i] += a[k][i].x, lo[4 * i + 1] += a[k][i].y, lo[4 * i + 2] += a[k][i].z, lo[4 * i + 3] += a[k][i].w;
+          hi[4 * i] += b[k][i].x, hi[4 * i + 1] += b[k][i].y, hi[4 * i + 2] += b[k][i].z, hi[4 * i + 3] += b[k][i].w;
+        }
+      }
+  }
+}
+
+__device__ inline void rope16(const float* cs_row, int seg, float (&lo)[16], float (&hi)[16]) {
+  const float* c = cs_row + 32 * seg;  // [i][cos, sin] for i = 16*seg ..
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float cv = c[2 * i], sv = c[2 * i + 1];
+    float a = lo[i], b = hi[i];
+    lo[i] = a * cv - b * sv;
+    hi[i] = b * cv + a * sv;
+  }
+}
+
+// qkv.p == NULL: q holds the rotated queries and the cache already holds the tree rows (separate RoPE kernel).
+// qkv.p != NULL: the kernel starts from the QKV GEMM's partial sums: it reduces them, rotates q and k (RoPE,
+// cos/sin table cs [row][64][2]), keeps q in LDS, and — if its key range reaches the tree slots — writes the 64
+// tree rows of K and V of its head into the cache before reading them back like any other key.  Workgroups of
+// the same head that both reach the tree slots write identical values.
 __global__ void __launch_bounds__(256)
-    attn_tree_mfma_kernel(int tree, const bf16_t* __restrict__ q, KvGeom g, const bf16_t* __restrict__ kc,
-                          const bf16_t* __restrict__ vc, int layer, const int32_t* __restrict__ seq_len,
-                          int max_prefix, bf16_t* __restrict__ att_out, float* __restrict__ part_o,
-                          float* __restrict__ part_ml) {
+    attn_tree_mfma_kernel(int tree, const bf16_t* __restrict__ q, const Partials qkv, const float* __restrict__ cs,
+                          KvGeom g, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int layer,
+                          const int32_t* __restrict__ seq_len, int max_prefix, bf16_t* __restrict__ att_out,
+                          float* __restrict__ part_o, float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   const TreeTables& t = c_trees[tree];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -54,14 +106,44 @@ __global__ void __launch_bounds__(256)
   // Q tile of this head -> LDS (rows padded by 16 B: the 16 B-per-lane operand reads below are bank-conflict
   // free).  The region is reused by the wave merge after the key loop.
   uint8_t* q_lds = reinterpret_cast<uint8_t*>(lds);
+  if (qkv.p == nullptr) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int idx = threadIdx.x + i * 256;
-    int row = idx >> 4, col = idx & 15;
-    *reinterpret_cast<u32x4*>(q_lds + row * kQRow + col * 16) =
-        *reinterpret_cast<const u32x4*>(q + (int64_t)(b * kTQ + row) * d + h * kHD + col * 8);
+    for (int i = 0; i < 4; ++i) {
+      int idx = threadIdx.x + i * 256;
+      int row = idx >> 4, col = idx & 15;
+      *reinterpret_cast<u32x4*>(q_lds + row * kQRow + col * 16) =
+          *reinterpret_cast<const u32x4*>(q + (int64_t)(b * kTQ + row) * d + h * kHD + col * 8);
+    }
+  } else {
+    const int row = threadIdx.x >> 2, seg = threadIdx.x & 3;
+    const int64_t grow = (int64_t)b * kTQ + row;
+    const float* cs_row = cs + grow * kHD;  // 64 pairs x 2
+    float lo[16], hi[16];
+    qkv_gather(qkv, grow, h * kHD, seg, lo, hi);
+    rope16(cs_row, seg, lo, hi);
+    uint8_t* qrow = q_lds + row * kQRow;
+    *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack_bf16x8(lo);
+    *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack_bf16x8(lo + 8);
+    *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack_bf16x8(hi);
+    *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack_bf16x8(hi + 8);
+    if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
+      const int slot = S + row;
+      qkv_gather(qkv, grow, d + h * kHD, seg, lo, hi);
+      rope16(cs_row, seg, lo, hi);
+      // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg)) = pack_bf16x8(lo);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg + 8)) = pack_bf16x8(lo + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg)) = pack_bf16x8(hi);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi + 8);
+      qkv_gather(qkv, grow, 2 * d + h * kHD, seg, lo, hi);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        vc[v_index(g, layer, b, h, slot, 16 * seg + i)] = float_to_bf16(lo[i]);
+        vc[v_index(g, layer, b, h, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[i]);
+      }
+    }
   }
-  __syncthreads();
+  __syncthreads();  // Q tile complete; the tree rows written above are complete (stores drain before a barrier)
   // B operand of scores^T: lane holds query 32u + qi, features 16ks + 8gh .. +7
   const uint8_t* qfrag = q_lds + qi * kQRow + gh * 16;
   const uint64_t mq[2] = {t.anc_mask[qi], t.anc_mask[32 + qi]};
@@ -287,6 +369,8 @@ bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
 }
 
 static int attn_splits(int B, int n_heads, int max_prefix) {
+  static const char* env = getenv("MDZ_ATTN_SPLITS");  // development knob
+  if (env && atoi(env) > 0) return atoi(env);
   int nb = (max_prefix + kTQ + 31) / 32;
   int by_len = nb / 8;                               // >= 2 blocks per wave
   int by_fill = (512 + B * n_heads - 1) / (B * n_heads);  // aim at ~512 workgroups
@@ -301,9 +385,9 @@ int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
 }
 
-int launch_attention_mfma(int tree, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
-                          const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
-                          int64_t scratch_bytes, hipStream_t st) {
+int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
+                          void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                          void* scratch, int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
   static bool attr_set = false;
@@ -318,9 +402,10 @@ int launch_attention_mfma(int tree, const void* q, const KvGeom& g, const void* 
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kTQ * kHD;
   dim3 grid(splits, g.n_heads, B);
-  attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, g, (const bf16_t*)kc,
-                                                          (const bf16_t*)vc, layer, seq_len, max_prefix,
-                                                          (bf16_t*)att_out, part_o, part_ml);
+  const Partials none{nullptr, 0, 0, 0, nullptr, 1};
+  attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, qkv ? *qkv : none, cs, g, (bf16_t*)kc,
+                                                          (bf16_t*)vc, layer, seq_len, max_prefix, (bf16_t*)att_out,
+                                                          part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
     attn_combine_kernel<<<dim3(g.n_heads, B), 256, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);

@@ -188,6 +188,67 @@ __global__ void rope_kvwrite_kernel(int tree, Partials part, const float* __rest
   }
 }
 
+// bf16 / head_dim 128 / tiled cache: one thread per (head, matrix, 4 rotary pairs), all partial-sum slots of its
+// two float4 in flight at once.  grid (rows, n_heads / 4), 192 threads.
+constexpr int kMaxSlots = 8;
+__device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
+  return uint2{(uint32_t)float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16),
+               (uint32_t)float_to_bf16(c).bits | ((uint32_t)float_to_bf16(d).bits << 16)};
+}
+__global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partials part, const float* __restrict__ cs,
+                                                               bf16_t* __restrict__ q_out, KvGeom g,
+                                                               bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+                                                               int layer, const int32_t* __restrict__ seq_len,
+                                                               int max_prefix) {
+  const TreeTables& t = c_trees[tree];
+  const int row = blockIdx.x, h = blockIdx.y * 4 + threadIdx.x / 48, w = threadIdx.x % 48;
+  const int which = w / 16, i = (w % 16) * 4;  // matrix (q,k,v) and first of 4 features; partner at i + 64
+  const int b = row / t.T, n = row % t.T;
+  const int d = g.n_heads * 128;
+  const int S = min(max(seq_len[b], 0), max_prefix);
+  const int slot = S + n;
+  const int col = which * d + h * 128 + i;
+  const float* src = part.p + (int64_t)row * 3 * d + col;
+  const int n_part = part.count(col);
+  float4 lo[kMaxSlots], hi[kMaxSlots];
+#pragma unroll
+  for (int p = 0; p < kMaxSlots; ++p)
+    if (p < n_part) {
+      lo[p] = *reinterpret_cast<const float4*>(src + (int64_t)p * part.stride);
+      hi[p] = *reinterpret_cast<const float4*>(src + (int64_t)p * part.stride + 64);
+    }
+  const float4 c01 = *reinterpret_cast<const float4*>(cs + ((int64_t)row * 64 + i) * 2);      // c0 s0 c1 s1
+  const float4 c23 = *reinterpret_cast<const float4*>(cs + ((int64_t)row * 64 + i) * 2 + 4);  // c2 s2 c3 s3
+  float4 a = {0.f, 0.f, 0.f, 0.f}, bq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < kMaxSlots; ++p)
+    if (p < n_part) {
+      a.x += lo[p].x, a.y += lo[p].y, a.z += lo[p].z, a.w += lo[p].w;
+      bq.x += hi[p].x, bq.y += hi[p].y, bq.z += hi[p].z, bq.w += hi[p].w;
+    }
+  if (which == 2) {
+    const float va[4] = {a.x, a.y, a.z, a.w}, vb[4] = {bq.x, bq.y, bq.z, bq.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vc[v_index(g, layer, b, h, slot, i + e)] = float_to_bf16(va[e]);
+      vc[v_index(g, layer, b, h, slot, i + 64 + e)] = float_to_bf16(vb[e]);
+    }
+    return;
+  }
+  const uint2 rlo = pack_bf16x4(a.x * c01.x - bq.x * c01.y, a.y * c01.z - bq.y * c01.w, a.z * c23.x - bq.z * c23.y,
+                                a.w * c23.z - bq.w * c23.w);
+  const uint2 rhi = pack_bf16x4(bq.x * c01.x + a.x * c01.y, bq.y * c01.z + a.y * c01.w, bq.z * c23.x + a.z * c23.y,
+                                bq.w * c23.z + a.w * c23.w);
+  if (which == 0) {
+    bf16_t* qo = q_out + (int64_t)row * d + h * 128 + i;
+    *reinterpret_cast<uint2*>(qo) = rlo;
+    *reinterpret_cast<uint2*>(qo + 64) = rhi;
+  } else {  // 4 consecutive features of one key are 8 contiguous bytes of the tiled K layout
+    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, h, slot, i)) = rlo;
+    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, h, slot, i + 64)) = rhi;
+  }
+}
+
 int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* cs, void* q_out, const KvGeom& g,
                         void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix,
                         hipStream_t st) {
@@ -196,7 +257,11 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   if (B == 0) return MDZ_OK;
   dim3 grid(B * t->T, g.n_heads);
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
-  if (dtype == MDZ_BF16)
+  if (dtype == MDZ_BF16 && g.tiled && g.head_dim == 128 && g.n_heads % 4 == 0 && qkv.n <= kMaxSlots &&
+      qkv.stride % 4 == 0 && (qkv.counts == nullptr || qkv.band_cols % 128 == 0))
+    rope_kvwrite_vec_kernel<<<dim3(B * t->T, g.n_heads / 4), 192, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc,
+                                                                          (bf16_t*)vc, layer, seq_len, max_prefix);
+  else if (dtype == MDZ_BF16)
     rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
                                                           layer, seq_len, max_prefix);
   else
@@ -225,12 +290,41 @@ __global__ void swiglu_kernel(Partials part, T* __restrict__ u, int M, int F) {
   u[idx] = from_float<T>(silu_f(gv) * uv);
 }
 
+// bf16: one thread per 4 features, gate and up float4 of every slot in flight at once
+__global__ void __launch_bounds__(256) swiglu_vec_kernel(Partials part, bf16_t* __restrict__ u, int M, int F) {
+  const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (idx >= (int64_t)M * F) return;
+  const int f = (int)(idx % F);
+  const int64_t m = idx / F;
+  const int64_t col = (int64_t)(2 * (f / 32)) * 32 + f % 32;
+  const float* src = part.p + m * 2 * F + col;
+  const int n_part = part.count((int)col);
+  float4 gt[kMaxSlots], up[kMaxSlots];
+#pragma unroll
+  for (int p = 0; p < kMaxSlots; ++p)
+    if (p < n_part) {
+      gt[p] = *reinterpret_cast<const float4*>(src + (int64_t)p * part.stride);
+      up[p] = *reinterpret_cast<const float4*>(src + (int64_t)p * part.stride + 32);
+    }
+  float4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < kMaxSlots; ++p)
+    if (p < n_part) {
+      a.x += gt[p].x, a.y += gt[p].y, a.z += gt[p].z, a.w += gt[p].w;
+      b.x += up[p].x, b.y += up[p].y, b.z += up[p].z, b.w += up[p].w;
+    }
+  *reinterpret_cast<uint2*>(u + idx) = pack_bf16x4(silu_f(a.x) * b.x, silu_f(a.y) * b.y, silu_f(a.z) * b.z, silu_f(a.w) * b.w);
+}
+
 int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStream_t st) {
   ProfScope prof_(PROF_SWIGLU, st);
   int64_t total = (int64_t)M * F;
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
-  if (dtype == MDZ_BF16)
+  // gate and up tiles of a pair lie in the same band (band widths are multiples of 64), so one count serves both
+  if (dtype == MDZ_BF16 && F % 32 == 0 && gu.n <= kMaxSlots && gu.stride % 4 == 0 && (gu.counts == nullptr || gu.band_cols % 64 == 0))
+    swiglu_vec_kernel<<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(gu, (bf16_t*)u, M, F);
+  else if (dtype == MDZ_BF16)
     swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);
   else
     swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu, (float*)u, M, F);

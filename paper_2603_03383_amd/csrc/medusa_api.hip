@@ -35,7 +35,10 @@ int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int
   res->counts = nullptr;
   res->band_cols = 1;
   if (gemm_mfma_supported(dtype, M, N, K)) {
-    if (max_split > 1) res->counts = counts;
+    if (max_split > 1) {
+      res->counts = counts;
+      res->n = max_split;  // upper bound; the per-band counts decide
+    }
     return launch_gemm_mfma(X, Wp, out, M, N, K, ld, res->stride, max_split, max_split > 1 ? counts : nullptr,
                             &res->band_cols, st);
   }
@@ -47,9 +50,9 @@ static int max_split_for(int rows) { return rows <= 64 ? 8 : 1; }
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g);
 int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix);
-int launch_attention_mfma(int tree, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
-                          const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
-                          int64_t scratch_bytes, hipStream_t st);
+int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
+                          void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                          void* scratch, int64_t scratch_bytes, hipStream_t st);
 
 int64_t tree_attention_scratch_bytes(int dtype, int tree, const KvGeom& g, int B, int max_prefix) {
   return attn_mfma_supported(dtype, tree, g) ? attn_mfma_scratch_bytes(B, g.n_heads, max_prefix) : 0;
@@ -59,9 +62,25 @@ int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, c
                           int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                           int64_t scratch_bytes, hipStream_t st) {
   if (attn_mfma_supported(dtype, tree, g))
-    return launch_attention_mfma(tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch, scratch_bytes,
-                                 st);
+    return launch_attention_mfma(tree, q, nullptr, nullptr, g, (void*)kc, (void*)vc, layer, seq_len, B, max_prefix,
+                                 att_out, scratch, scratch_bytes, st);
   return launch_attention_generic(dtype, tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, st);
+}
+
+// QKV partial sums -> RoPE -> cache rows -> attention.  One fused kernel where the MFMA attention applies (the
+// partial sums must then come in 128-column bands so that a head's columns share one slot count).
+int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float* cs, void* q_scratch, const KvGeom& g,
+                          void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                          void* scratch, int64_t scratch_bytes, hipStream_t st) {
+  static const bool unfused = getenv("MDZ_UNFUSED_ROPE") != nullptr;  // development knob
+  if (!unfused && attn_mfma_supported(dtype, tree, g) && qkv.stride % 4 == 0 && qkv.ld % 4 == 0 &&
+      (qkv.counts == nullptr || qkv.band_cols % 128 == 0))
+    return launch_attention_mfma(tree, nullptr, &qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
+                                 scratch_bytes, st);
+  int rc = launch_rope_kvwrite(dtype, tree, qkv, cs, q_scratch, g, kc, vc, layer, seq_len, B, max_prefix, st);
+  if (rc) return rc;
+  return launch_tree_attention(dtype, tree, q_scratch, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
+                               scratch_bytes, st);
 }
 
 // ---- workspace ------------------------------------------------------------------------------------
@@ -167,9 +186,7 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   void* u = ws + w.u;
   Partials pr;
   if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, 3 * m.d, m.d, 3 * m.d, ms, cnt, &pr, st))) return rc;
-  if ((rc = launch_rope_kvwrite(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, st)))
-    return rc;
-  if ((rc = launch_tree_attention(m.dtype, m.tree, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
+  if ((rc = launch_rope_attention(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
                                   ws + w.attn_scratch, w.total - w.attn_scratch, st)))
     return rc;
   if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, cnt, &pr, st))) return rc;
