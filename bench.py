@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E peak
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
+# of known size; see profiles/gemm_w64_cfg3_step_1k_pmc.md).  Measured offline; not re-measured by this script.
+TRAFFIC_W64 = {"fetch_bytes_per_launch": 162.84e6, "write_bytes_per_launch": 12.32e6,
+               "source": "profiles/gemm_w64_cfg3_step_1k_pmc.md"}
 
 
 def algorithmic_bytes(w, with_heads: bool):
@@ -38,7 +42,11 @@ def algorithmic_bytes(w, with_heads: bool):
     kv_prefix = sum(w.prefix) * kv_row * w.n_layers
     kv_tree = 2 * w.batch * T * kv_row * w.n_layers               # written + read
     embed = w.batch * T * w.d * es
-    return dict(gemm=gemm_layers + lm + heads, weights_layers=gemm_layers, lm_head=lm, heads=heads,
+    es_ = es
+    gemm_w64 = w.n_layers * (3 * w.d * w.d + 2 * w.d * w.ffn) * es_ + lm       # QKV, gate/up, LM head launches
+    gemm_n64 = w.n_layers * (w.d * w.d + w.d * w.ffn) * es_                    # O, down launches
+    return dict(gemm=gemm_layers + lm + heads, gemm_w64=gemm_w64, gemm_n64=gemm_n64,
+                weights_layers=gemm_layers, lm_head=lm, heads=heads,
                 kv_prefix=kv_prefix, kv_tree=kv_tree, embed=embed,
                 total=gemm_layers + lm + heads + kv_prefix + kv_tree + embed)
 
@@ -186,13 +194,22 @@ def main():
     prof = P.medusa_profile_end()
     torch.cuda.synchronize()
 
+    # practical read ceiling of this machine, measured now: the library's pure-read stream at 1 GB and at the dominant
+    # kernel's average size
+    from paper_2603_03383_amd.stream_calib import read_ceiling
+    ceil = read_ceiling(sizes=(154_500_000, 1_048_576_000), pool_bytes=4 << 30)
+
     ab = algorithmic_bytes(w, with_heads)
     if layer_only:
         ab["gemm"] = ab["weights_layers"]
+        ab["gemm_w64"] -= ab["lm_head"]
         ab["total"] = ab["weights_layers"] + ab["kv_prefix"] + ab["kv_tree"]
-    gemm = prof.get("gemm", dict(launches=0, total_us=0.0))
+    # dominant kernel: gemm_mfma_kernel<4,1,2,*> (QKV, gate/up and LM-head launches: 128-column bands, 64 rows)
+    gemm = prof.get("gemm_w64", dict(launches=0, total_us=0.0))
     gemm_us_per_step = gemm["total_us"] / args.steps
-    gemm_gbps = ab["gemm"] / (gemm_us_per_step * 1e-6) / 1e9 if gemm_us_per_step else 0.0
+    gemm_gbps = ab["gemm_w64"] / (gemm_us_per_step * 1e-6) / 1e9 if gemm_us_per_step else 0.0
+    all_gemm_us = sum(v["total_us"] for k, v in prof.items() if k.startswith("gemm")) / args.steps
+    all_gemm_gbps = ab["gemm"] / (all_gemm_us * 1e-6) / 1e9 if all_gemm_us else 0.0
     step_gbps = ab["total"] / (ms * 1e-3) / 1e9
 
     out = {
@@ -205,12 +222,20 @@ def main():
         "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
                 "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
                 "kv_share_of_bytes": (ab["kv_prefix"] + ab["kv_tree"]) / ab["total"]},
-        "roofline": {"kernel": "gemm (all weight-streaming GEMM launches of a step)", "bound": "hbm",
-                     "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gemm_gbps / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_step": ab["gemm"], "launches_per_step": gemm["launches"] / args.steps,
-                     "avg_launch_us": gemm["total_us"] / max(1, gemm["launches"])},
+        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,256> (gemm_w64: QKV, gate/up and LM-head launches)",
+                     "bound": "hbm", "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gemm_gbps / HBM_PEAK_GBPS,
+                     "traffic": TRAFFIC_W64["fetch_bytes_per_launch"] + TRAFFIC_W64["write_bytes_per_launch"],
+                     "traffic_detail": TRAFFIC_W64,
+                     "algorithmic_bytes_per_launch": ab["gemm_w64"] / max(1.0, gemm["launches"] / args.steps),
+                     "launches_per_step": gemm["launches"] / args.steps,
+                     "avg_launch_us": gemm["total_us"] / max(1, gemm["launches"]),
+                     "all_gemm_launches_GBps": all_gemm_gbps,
+                     "measured": "HIP events on the launch stream around every launch, %d instrumented steps "
+                                 "after the timed region" % args.steps},
+        "stream_read_ceiling_GBps": {"%.0fMB" % (k / 1e6): v for k, v in ceil.items()},
         "kernel_us_per_step": {k: v["total_us"] / args.steps for k, v in prof.items()},
+        "kernel_launches_per_step": {k: v["launches"] / args.steps for k, v in prof.items()},
         "paper_context": "paper reports only ratios: 1.35x end-to-end on an NPU, fp16, L=128 (not comparable)",
     }
     if not args.skip_cpu_baseline:

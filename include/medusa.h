@@ -119,9 +119,23 @@ const char* medusa_last_error(void);
 int medusa_profile_begin(int max_launches);
 
 /* Stops recording, waits for the recorded events, and writes one text line per kernel family into the HOST
- * buffer `report`: "name,launches,total_us,min_us,max_us\n" (families: gemm, attention, rmsnorm, rope,
- * swiglu, embed, select, accept, kv_compact, misc). */
+ * buffer `report`: "name,launches,total_us,min_us,max_us\n" (families: gemm_w64 / gemm_n64 / gemm_w32 /
+ * gemm_n32 = the weight-streaming GEMM instantiated for 128- or 64-column bands and 64 or <= 32 rows,
+ * gemm_portable, attention, rmsnorm, rope, swiglu, embed, select, accept, kv_compact, misc). */
 int medusa_profile_end(char* report, int64_t report_bytes);
+
+/* ---- calibration streams (benchmarks only) --------------------------------------------------- */
+
+/* Enqueues a pure read of `bytes` bytes at src (16 bytes per lane, every wave a contiguous range, n_workgroups
+ * workgroups of 256 threads): the practical HBM read ceiling the weight-streaming kernels are compared with.
+ * Only medusa_stream_read_bytes(bytes, n_workgroups) bytes are read (whole 8 KiB rounds per wave).  sink4: 4
+ * device bytes that keep the loads alive. */
+int medusa_stream_read(const void* src, int64_t bytes, int n_workgroups, void* sink4, void* stream);
+int64_t medusa_stream_read_bytes(int64_t bytes, int n_workgroups);
+
+/* Enqueues a plain copy of `bytes` (multiple of 16) from src to dst: a transfer of known size for scaling
+ * hardware byte counters. */
+int medusa_stream_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
 /* ---- weight packing (one-time, outside any timed region) ------------------------------------ */
 

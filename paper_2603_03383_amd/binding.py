@@ -60,6 +60,9 @@ _SIGNATURES = {
     "medusa_last_error": (C.c_char_p, []),
     "medusa_profile_begin": (C.c_int, [C.c_int]),
     "medusa_profile_end": (C.c_int, [C.c_char_p, C.c_int64]),
+    "medusa_stream_read": (C.c_int, [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
+    "medusa_stream_read_bytes": (C.c_int64, [C.c_int64, C.c_int]),
+    "medusa_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "medusa_pack_tile_rows": (C.c_int, [C.c_int]),
     "medusa_packed_bytes": (C.c_int64, [C.c_int, C.c_int64, C.c_int64]),
     "medusa_pack_weight": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
@@ -156,6 +159,16 @@ def medusa_profile_end() -> dict:
         name, n, tot, mn, mx = line.split(",")
         out[name] = dict(launches=int(n), total_us=float(tot), min_us=float(mn), max_us=float(mx))
     return out
+
+
+def medusa_stream_read(src: torch.Tensor, nbytes: int, n_workgroups: int, sink4: torch.Tensor, stream=None) -> int:
+    """Enqueues the read stream over the first nbytes of src; returns the bytes actually read."""
+    _check(lib().medusa_stream_read(_ptr(src), nbytes, n_workgroups, _ptr(sink4), _stream(stream)))
+    return lib().medusa_stream_read_bytes(nbytes, n_workgroups)
+
+
+def medusa_stream_copy(src: torch.Tensor, dst: torch.Tensor, nbytes: int, stream=None) -> None:
+    _check(lib().medusa_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
 
 
 def medusa_pack_tile_rows(dtype: int) -> int:

@@ -261,8 +261,9 @@ int gemm_mfma_band_cols(int M, int N, int K, int max_split) {
 // the number of slots written for each band of `*band_cols` columns (1 everywhere when max_split <= 1).
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
                      int max_split, int32_t* counts, int* band_cols, hipStream_t st) {
-  ProfScope prof_(PROF_GEMM, st);
   GemmPlan p = plan_gemm(M, N, K, max_split);
+  ProfScope prof_(p.mt == 2 ? (p.wpb == 4 ? PROF_GEMM_W64 : PROF_GEMM_N64) : (p.wpb == 4 ? PROF_GEMM_W32 : PROF_GEMM_N32),
+                  st);
   const int n_tiles = N / 32, n_stages = K / p.ck;
   *band_cols = p.wpb * p.nt * 32;
   const bf16_t* x = (const bf16_t*)X;
