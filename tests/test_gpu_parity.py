@@ -379,3 +379,137 @@ def test_empty_batch_and_bad_arguments():
     assert e.value.status == -2
     torch.cuda.synchronize()
     assert int(seq_len[0]) == 64
+
+
+# ------------------------------------------------------------------------------------------------
+# config 3 at full depth, config 4 (long prefix), config 5 (ragged batch), full-size properties
+# ------------------------------------------------------------------------------------------------
+
+def _oracle_step_streamed(w, tokens, S, tree, kv_rows=None):
+    """The oracle's verify step with layer weights generated one layer at a time (bounded host memory).
+    Returns logits, hidden, node_argmax and (optionally) the KV rows written by chosen layers."""
+    cfg = U.oracle_cfg(w)
+    T = tree["T"]
+    emb = W.embedding(w, G.DEV)[torch.as_tensor(np.asarray(tokens), device=G.DEV).long()]
+    x = U.to_np(emb).astype(np.float64)
+    kept = {}
+    for l in range(w.n_layers):
+        lw = U.oracle_layer(w, l, device=G.DEV)
+        k, v = W.prefix_kv(w, l, 0, G.DEV)
+        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc[:, :S] = U.to_np(k); vc[:, :S] = U.to_np(v)
+        x = O.tree_verify_layer(x, lw, kc, vc, S, tree, cfg)
+        if kv_rows is not None and l in kv_rows:
+            kept[l] = (kc[:, S:].copy(), vc[:, S:].copy())
+    hidden = O.rmsnorm(x, np.ones(w.d), w.rms_eps)
+    logits = hidden @ U.to_np(W.lm_head(w, G.DEV)).astype(np.float64).T
+    return dict(logits=logits, hidden=hidden, node_argmax=O.argmax_lowest(logits), kv=kept)
+
+
+def test_cfg3_full_depth_32_layers_every_logit():
+    """The metric's own workload: 32 layers, prefix 1024, all 64 x 128000 logits against the oracle."""
+    w = W.CONFIGS["cfg3_step_1k"]
+    S = w.prefix[0]
+    tol = TOL["bf16"]
+    tree = U.oracle_tree(w)
+    T = tree["T"]
+    tokens = W.random_tokens(w, "full_depth_tree", (T,)).numpy()
+    ref = _oracle_step_streamed(w, tokens, S, tree, kv_rows={0, 31})
+    dm = G.device_model(w, heads=False)
+    kv = G.device_kv_random_prefix(dm, w, cap=S + T)
+    buf = P.StepBuffers(dm, 1, S, want_logits=True)
+    buf.tree_tokens.copy_(_i32(tokens).view(1, T))
+    seq_len = _i32([S])
+    P.run_step(dm, kv, buf, None, None, None, seq_len, with_heads=False)
+    torch.cuda.synchronize()
+    lg = buf.logits[0].cpu().numpy()
+    scale = _scale(ref["logits"])
+    err = np.abs(lg - ref["logits"]).max()
+    print(f"cfg3 full depth: logits err/scale {err / scale:.3e}")
+    assert err <= tol * scale
+    assert np.abs(U.to_np(buf.hidden[0]) - ref["hidden"]).max() <= tol * _scale(ref["hidden"])
+    gpu_am = buf.node_argmax[0].cpu().numpy()
+    check_argmax_near_tie(gpu_am, lg, ref["logits"], tol * scale)
+    acc = O.accept_longest_prefix(tree, tokens, gpu_am)
+    assert int(buf.accept_len[0]) == acc["accept_len"] and int(seq_len[0]) == S + acc["accept_len"]
+    # compaction ran after the pass (node 0 stays in place): row S is the root's row
+    for l, (kr, vr) in ref["kv"].items():
+        k, v = kv.read(l, 0, S, 1)
+        assert np.abs(U.to_np(k) - kr[:, :1]).max() <= tol * _scale(kr) and np.abs(U.to_np(v) - vr[:, :1]).max() <= tol * _scale(vr)
+    # run-to-run determinism of the whole step at full size (fixed-order reductions everywhere)
+    kv2 = G.device_kv_random_prefix(dm, w, cap=S + T)
+    buf2 = P.StepBuffers(dm, 1, S, want_logits=True)
+    buf2.tree_tokens.copy_(_i32(tokens).view(1, T))
+    seq2 = _i32([S])
+    P.run_step(dm, kv2, buf2, None, None, None, seq2, with_heads=False)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.logits, buf2.logits) and torch.equal(buf.node_argmax, buf2.node_argmax)
+    # sibling relabelling at full size: nodes 8 and 9 (each with one child: 39, 40) are isomorphic subtrees
+    assert tree["parent"][39] == 8 and tree["parent"][40] == 9 and not (tree["parent"] == 39).any()
+    perm = np.arange(T); perm[[8, 9, 39, 40]] = [9, 8, 40, 39]
+    kv3 = G.device_kv_random_prefix(dm, w, cap=S + T)
+    buf2.tree_tokens.copy_(_i32(tokens[perm]).view(1, T))
+    seq2.copy_(_i32([S]))
+    P.run_step(dm, kv3, buf2, None, None, None, seq2, with_heads=False)
+    torch.cuda.synchronize()
+    lg3 = buf2.logits[0].cpu().numpy()
+    assert np.abs(lg3 - lg[perm]).max() <= 2e-3 * scale
+
+
+@pytest.mark.parametrize("S", [4096, 16384])
+def test_cfg4_long_prefix_full_size_layer(S):
+    w = W.CONFIGS["cfg4_step_16k"].with_(n_layers=1, prefix=(S,))
+    r = _layer_case(w, [S], S, x_seed=f"long_x{S}")
+    rel = _check_layer(r, [S], "bf16")
+    print(f"cfg4 layer S={S}: max error / scale = {rel:.3e}")
+
+
+def test_cfg5_ragged_batch_16_sequences():
+    """16 sequences with seeded ragged prefixes (256..4096), one 7B-shaped layer + LM head + heads + accept +
+    per-sequence compaction.  rows = 1024 > 64, so the GEMMs take the portable kernels."""
+    w = W.CONFIGS["cfg5_ragged_b16"].with_(n_layers=1)
+    Bn = w.batch
+    tol = TOL["bf16"]
+    tree = U.oracle_tree(w)
+    T, K = tree["T"], tree["K"]
+    max_prefix = max(w.prefix)
+    dm = G.device_model(w)
+    kv = G.device_kv_random_prefix(dm, w, cap=max_prefix + T)
+    model = U.oracle_model(w, device=G.DEV)
+    h = W.hidden_state(w, "ragged_h", Bn, device=G.DEV)
+    buf = P.StepBuffers(dm, Bn, max_prefix, want_logits=True, want_head_logits=True)
+    seq_len = _i32(list(w.prefix))
+    P.run_step(dm, kv, buf, h.view(Bn, 1, -1), None, None, seq_len)
+    torch.cuda.synchronize()
+    hl = buf.head_logits.cpu().numpy()
+    cand = buf.cand_flat.cpu().numpy()
+    toks = buf.tree_tokens.cpu().numpy()
+    lgs = buf.logits.cpu().numpy()
+    ams = buf.node_argmax.cpu().numpy()
+    worst = 0.0
+    for b in range(Bn):
+        S = w.prefix[b]
+        heads = O.medusa_heads(U.to_np(h)[b], model, tree)
+        hscale = _scale(heads["head_logits"])
+        assert np.abs(hl[b] - heads["head_logits"]).max() <= tol * hscale
+        off = 1
+        check_argmax_near_tie(cand[b, :1], hl[b, :1], heads["head_logits"][:1], tol * hscale)
+        for k in range(K):
+            c = tree["caps"][k]
+            check_topk_near_tie(cand[b, off:off + c], hl[b, k + 1], heads["head_logits"][k + 1], c, tol * hscale)
+            off += c
+        assert toks[b].tolist() == cand[b][tree["cand_slot"]].tolist()
+        kc, vc = U.oracle_prefix_cache(w, b, S + T, device=G.DEV)
+        ref = O.tree_verify_step(toks[b], model, kc, vc, S, tree)
+        scale = _scale(ref["logits"])
+        err = np.abs(lgs[b] - ref["logits"]).max()
+        worst = max(worst, err / scale)
+        assert err <= tol * scale
+        check_argmax_near_tie(ams[b], lgs[b], ref["logits"], tol * scale)
+        acc = O.accept_longest_prefix(tree, toks[b], ams[b])
+        assert int(buf.accept_len[b]) == acc["accept_len"] and int(seq_len[b]) == S + acc["accept_len"]
+        assert buf.acc_nodes[b].cpu().numpy().tolist() == acc["acc_nodes"].tolist()
+        assert buf.kv_src_slots[b].cpu().numpy().tolist() == [S + n if n >= 0 else -1 for n in acc["acc_nodes"]]
+        k, v = kv.read(0, b, S, 1)
+        assert np.abs(U.to_np(k) - kc[0][:, S:S + 1]).max() <= tol * _scale(kc[0][:, S:S + T])
+    print(f"cfg5 ragged batch: worst logits err/scale {worst:.3e}")
