@@ -142,7 +142,7 @@ int medusa_stream_copy(const void* src, void* dst, int64_t bytes, void* stream);
 /* Rows per packed tile for a dtype (32 for bf16, 16 for fp32). */
 int medusa_pack_tile_rows(int dtype);
 
-/* Bytes of a packed [n_rows, k] matrix (n_rows and k rounded up to the tile sizes; padding is zero). */
+/* Bytes of a packed [n_rows, k] matrix (bf16: n_rows rounded up to 128 and k to 256; fp32: n_rows to 16). */
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
 
 /* Re-tiles a ROW-MAJOR [n_rows, k] matrix `src` (row r = output feature r, contiguous over input

@@ -68,14 +68,19 @@ __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
 inline int elem_bytes(int dtype) { return dtype == MDZ_BF16 ? 2 : 4; }
 
 // ---- packed weight layout ----------------------------------------------------------------------
-// bf16: tiles of 32 rows.  A tile is a sequence of k-steps of 16 input features; one k-step is a
-// 1 KiB block = 64 lanes x 8 bf16: lane l holds row (l % 32), features 16*ks + 8*(l / 32) .. +7.
-// This is the B-operand order of the 32x32x16 bf16 MFMA, so a wave streams a tile with fully
-// coalesced 16-byte-per-lane loads and no shuffling.
+// bf16: rows are grouped in tiles of 32 and tiles in bands of 4 (128 output columns); input features in
+// k-steps of 16 and k-steps in stages of 16 (256 features).  Memory order: [band][stage][tile in band][k-step
+// in stage][lane][8 bf16], where one k-step of one tile is a 1 KiB block of 64 lanes x 8 bf16: lane l holds row
+// (l % 32), features 16*ks + 8*(l / 32) .. +7 — the B-operand order of the 32x32x16 bf16 MFMA.  So a wave loads
+// a k-step with one fully coalesced 16-byte-per-lane instruction and no shuffling, the four waves of a workgroup
+// read one contiguous 64 KiB block per stage, and successive stages of a band are contiguous: every workgroup
+// streams linear memory.  Rows are padded to 128 and features to 256 (zero filled where the kernels read them).
 // fp32: tiles of 16 rows, plain row-major inside the matrix (the tile only matters for stacking).
 constexpr int kTileRowsBf16 = 32;
 constexpr int kTileRowsF32 = 16;
 constexpr int kKStepBf16 = 16;
+constexpr int kBandTiles = 4;      // tiles per band of the bf16 layout
+constexpr int kStageFeatures = 256;  // features per stage of the bf16 layout
 
 __host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
@@ -84,18 +89,22 @@ struct Packed;
 template <>
 struct Packed<bf16_t> {
   static constexpr int kTileRows = kTileRowsBf16;
-  // element (row n, feature k) of a packed matrix with kp = padded feature count
+  // element (row n, feature k) of a packed matrix with kp = padded feature count (multiple of 256)
   __host__ __device__ static inline int64_t index(int64_t n, int64_t k, int64_t kp) {
-    int64_t tile = n >> 5, r = n & 31, ks = k >> 4, kk = k & 15;
-    return (tile * (kp >> 4) + ks) * 512 + (r + 32 * (kk >> 3)) * 8 + (kk & 7);
+    int64_t tile = n >> 5, r = n & 31, band = tile >> 2, tin = tile & 3;
+    int64_t ks = k >> 4, kk = k & 15, st = ks >> 4, kin = ks & 15;
+    int64_t unit = ((band * (kp >> 8) + st) * kBandTiles + tin) * 16 + kin;  // 1 KiB units
+    return unit * 512 + (r + 32 * (kk >> 3)) * 8 + (kk & 7);
   }
-  __host__ __device__ static inline int64_t padded_k(int64_t k) { return round_up(k, kKStepBf16); }
+  __host__ __device__ static inline int64_t padded_k(int64_t k) { return round_up(k, kStageFeatures); }
+  __host__ __device__ static inline int64_t padded_rows(int64_t n) { return round_up(n, kTileRowsBf16 * kBandTiles); }
 };
 template <>
 struct Packed<float> {
   static constexpr int kTileRows = kTileRowsF32;
   __host__ __device__ static inline int64_t index(int64_t n, int64_t k, int64_t kp) { return n * kp + k; }
   __host__ __device__ static inline int64_t padded_k(int64_t k) { return k; }
+  __host__ __device__ static inline int64_t padded_rows(int64_t n) { return round_up(n, kTileRowsF32); }
 };
 
 // ---- KV cache layout ---------------------------------------------------------------------------

@@ -50,7 +50,7 @@ __global__ void __launch_bounds__(WPB * 64)
     u_hi = (int)((w + 1) * U / G);
   }
   if (u_lo >= u_hi) return;
-  const int64_t tile_elems = (int64_t)(K >> 4) * 512;  // bf16 elements of one packed 32-row tile
+  const int nst256 = (K + kStageFeatures - 1) / kStageFeatures;  // stages of the packed layout
 
   f32x16 acc[NT][MT];
   auto zero_acc = [&]() {
@@ -99,7 +99,10 @@ __global__ void __launch_bounds__(WPB * 64)
     for (int nt = 0; nt < NT; ++nt) {
       int tile = (b * WPB + wave) * NT + nt;
       tile = tile < n_tiles ? tile : 0;
-      const u32x4* p = reinterpret_cast<const u32x4*>(Wp + tile * tile_elems) + (int64_t)c * KS * 64 + lane;
+      // packed order [band of 4 tiles][stage of 256 features][tile in band][16 k-steps][lane]
+      const int st = CK == 256 ? c : (c >> 1), kin0 = CK == 256 ? 0 : (c & 1) * 8;
+      const int64_t unit = (((int64_t)(tile >> 2) * nst256 + st) * kBandTiles + (tile & 3)) * 16 + kin0;
+      const u32x4* p = reinterpret_cast<const u32x4*>(Wp) + unit * 64 + lane;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) dst[nt][ks] = p[ks * 64];
     }

@@ -34,19 +34,27 @@ int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int
   res->ld = ld;
   res->counts = nullptr;
   res->band_cols = 1;
-  if (gemm_mfma_supported(dtype, M, N, K)) {
+  const int rows_per_launch = M <= 64 ? M : 64;
+  if (gemm_mfma_supported(dtype, rows_per_launch, N, K) && (M <= 64 || M % 64 == 0)) {
     if (max_split > 1) {
       res->counts = counts;
       res->n = max_split;  // upper bound; the per-band counts decide
     }
-    return launch_gemm_mfma(X, Wp, out, M, N, K, ld, res->stride, max_split, max_split > 1 ? counts : nullptr,
-                            &res->band_cols, st);
+    // More than 64 rows (several sequences): one launch per block of 64 rows.  Every launch uses the same plan, so
+    // the slot counts are identical; the first launch streams the matrix from HBM, the following ones mostly from
+    // the memory-side cache.
+    for (int m0 = 0; m0 < M; m0 += rows_per_launch) {
+      int rc = launch_gemm_mfma((const char*)X + (int64_t)m0 * K * 2, Wp, out + (int64_t)m0 * ld, rows_per_launch, N, K, ld,
+                                res->stride, max_split, max_split > 1 ? counts : nullptr, &res->band_cols, st);
+      if (rc) return rc;
+    }
+    return MDZ_OK;
   }
   return launch_gemm_generic(dtype, X, Wp, out, M, N, K, ld, false, st);
 }
 
 // split-K is only worth its partial-sum traffic for skinny problems
-static int max_split_for(int rows) { return rows <= 64 ? 8 : 1; }
+static int max_split_for(int rows) { return (rows <= 64 || rows % 64 == 0) ? 8 : 1; }
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g);
 int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix);
@@ -248,7 +256,7 @@ int medusa_pack_tile_rows(int dtype) {
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k) {
   MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
   MDZ_REQUIRE(n_rows > 0 && k > 0, MDZ_EINVAL, "packed_bytes: sizes must be positive");
-  if (dtype == MDZ_BF16) return round_up(n_rows, kTileRowsBf16) * Packed<bf16_t>::padded_k(k) * 2;
+  if (dtype == MDZ_BF16) return Packed<bf16_t>::padded_rows(n_rows) * Packed<bf16_t>::padded_k(k) * 2;
   return round_up(n_rows, kTileRowsF32) * k * 4;
 }
 
