@@ -42,10 +42,8 @@ def algorithmic_bytes(w, with_heads: bool):
     kv_prefix = sum(w.prefix) * kv_row * w.n_layers
     kv_tree = 2 * w.batch * T * kv_row * w.n_layers               # written + read
     embed = w.batch * T * w.d * es
-    es_ = es
-    gemm_w64 = w.n_layers * (3 * w.d * w.d + 2 * w.d * w.ffn) * es_ + lm       # QKV, gate/up, LM head launches
-    gemm_n64 = w.n_layers * (w.d * w.d + w.d * w.ffn) * es_                    # O, down launches
-    return dict(gemm=gemm_layers + lm + heads, gemm_w64=gemm_w64, gemm_n64=gemm_n64,
+    gemm_w64 = gemm_layers + lm          # every 64-row launch: QKV, O, gate/up, down of each layer and the LM head
+    return dict(gemm=gemm_layers + lm + heads, gemm_w64=gemm_w64,
                 weights_layers=gemm_layers, lm_head=lm, heads=heads,
                 kv_prefix=kv_prefix, kv_tree=kv_tree, embed=embed,
                 total=gemm_layers + lm + heads + kv_prefix + kv_tree + embed)
@@ -204,7 +202,7 @@ def main():
         ab["gemm"] = ab["weights_layers"]
         ab["gemm_w64"] -= ab["lm_head"]
         ab["total"] = ab["weights_layers"] + ab["kv_prefix"] + ab["kv_tree"]
-    # dominant kernel: gemm_mfma_kernel<4,1,2,*> (QKV, gate/up and LM-head launches: 128-column bands, 64 rows)
+    # dominant kernel: gemm_mfma_kernel<4,1,2,128> (every 64-row GEMM launch: 128-column bands, 128-feature stages)
     gemm = prof.get("gemm_w64", dict(launches=0, total_us=0.0))
     gemm_us_per_step = gemm["total_us"] / args.steps
     gemm_gbps = ab["gemm_w64"] / (gemm_us_per_step * 1e-6) / 1e9 if gemm_us_per_step else 0.0
@@ -222,7 +220,7 @@ def main():
         "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
                 "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
                 "kv_share_of_bytes": (ab["kv_prefix"] + ab["kv_tree"]) / ab["total"]},
-        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,256> (gemm_w64: QKV, gate/up and LM-head launches)",
+        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head)",
                      "bound": "hbm", "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gemm_gbps / HBM_PEAK_GBPS,
                      "traffic": TRAFFIC_W64["fetch_bytes_per_launch"] + TRAFFIC_W64["write_bytes_per_launch"],
