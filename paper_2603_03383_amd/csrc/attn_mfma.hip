@@ -11,6 +11,10 @@
 // The tree mask is one 64-bit word per query (a compile-time table) tested only in blocks that reach
 // past the prefix.  Waves merge through LDS, key-splits through a small second kernel, both in a fixed
 // order, so results are deterministic.
+// Key-splits: when the kernel starts from the QKV partial sums, the last split owns every block that holds a
+// tree slot (it is the one that has to produce those K / V rows first) and the other splits share the blocks
+// that hold prefix keys only, which need nothing but Q: the long dependent chain (reduce K and V, write them,
+// read them back) then covers three blocks at most instead of an even share of the prefix.
 #include "kernels.h"
 
 namespace mdz {
@@ -21,7 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHD = 128;         // head_dim
 constexpr int kTQ = 64;          // queries (tree nodes)
-constexpr int kOPad = kTQ + 1;   // LDS row stride of the merge buffer (floats)
+constexpr int kOPad = kTQ + 2;   // LDS row stride of the merge buffer (floats): 66 keeps its writes and reads conflict free
 constexpr int kQRow = kHD * 2 + 16;  // bytes per staged Q row
 constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
 
@@ -39,33 +43,41 @@ __device__ inline u32x4 pack_bf16x8(const float* v) {
   return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
 }
 
-// One head-matrix (q, k or v of head h) of the QKV GEMM output for the prologue below: thread (row = t/4,
+// NM head-matrices (q, or q k v, of head h) of the QKV GEMM output for the prologue below: thread (row = t/4,
 // seg = t%4) sums the partial-sum slots (in order) of features [16*seg, 16*seg+16) and their rotary partners
-// [64 + 16*seg, ...): lo[16], hi[16].  Slots are fetched two at a time (16 float4 in flight per thread).
-__device__ inline void qkv_gather(const Partials& part, int64_t row, int col0, int seg, float (&lo)[16], float (&hi)[16]) {
-  const int n_part = part.count(col0);
+// [64 + 16*seg, ...) of each matrix: lo[m][16], hi[m][16].  The loads of one slot of all NM matrices are issued
+// together (8 float4 per matrix in flight per thread); matrix m starts at column col0 + m * col_step.
+template <int NM>
+__device__ inline void qkv_gather(const Partials& part, int64_t row, int col0, int col_step, int seg, float (&lo)[NM][16],
+                                  float (&hi)[NM][16]) {
+  int n_part[NM], n_max = 0;
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    n_part[m] = part.count(col0 + m * col_step);
+    n_max = n_part[m] > n_max ? n_part[m] : n_max;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lo[m][i] = hi[m][i] = 0.f;
+  }
   const float* src = part.p + row * part.ld + col0 + 16 * seg;
+  for (int p = 0; p < n_max; ++p) {
+    float4 a[NM][4], b[NM][4];
+    const float* sp = src + (int64_t)p * part.stride;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) lo[i] = hi[i] = 0.f;
-  for (int p0 = 0; p0 < n_part; p0 += 2) {
-    float4 a[2][4], b[2][4];
-#pragma unroll
-    for (int k = 0; k < 2; ++k)
-      if (p0 + k < n_part) {
-        const float* sp = src + (int64_t)(p0 + k) * part.stride;
+    for (int m = 0; m < NM; ++m)
+      if (p < n_part[m]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          a[k][i] = *reinterpret_cast<const float4*>(sp + 4 * i);
-          b[k][i] = *reinterpret_cast<const float4*>(sp + 64 + 4 * i);
+          a[m][i] = *reinterpret_cast<const float4*>(sp + m * col_step + 4 * i);
+          b[m][i] = *reinterpret_cast<const float4*>(sp + m * col_step + 64 + 4 * i);
         }
       }
 #pragma unroll
-    for (int k = 0; k < 2; ++k)
-      if (p0 + k < n_part) {
+    for (int m = 0; m < NM; ++m)
+      if (p < n_part[m]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          lo[4 * i] += a[k][i].x, lo[4 * i + 1] += a[k][i].y, lo[4 * i + 2] += a[k][i].z, lo[4 * i + 3] += a[k][i].w;
-          hi[4 * i] += b[k][i].x, hi[4 * i + 1] += b[k][i].y, hi[4 * i + 2] += b[k][i].z, hi[4 * i + 3] += b[k][i].w;
+          lo[m][4 * i] += a[m][i].x, lo[m][4 * i + 1] += a[m][i].y, lo[m][4 * i + 2] += a[m][i].z, lo[m][4 * i + 3] += a[m][i].w;
+          hi[m][4 * i] += b[m][i].x, hi[m][4 * i + 1] += b[m][i].y, hi[m][4 * i + 2] += b[m][i].z, hi[m][4 * i + 3] += b[m][i].w;
         }
       }
   }
@@ -101,7 +113,15 @@ __global__ void __launch_bounds__(256)
   const int S = min(max(seq_len[b], 0), max_prefix);
   const int n_slots = S + kTQ;
   const int nb = (n_slots + 31) >> 5;
-  const int blk_begin = (int)((int64_t)split * nb / n_splits), blk_end = (int)((int64_t)(split + 1) * nb / n_splits);
+  int blk_begin, blk_end;
+  if (qkv.p != nullptr && n_splits > 1) {  // last split: every block with a tree slot; the others: prefix-only blocks
+    const int pb = S >> 5, ps = n_splits - 1;
+    blk_begin = split == ps ? pb : (int)((int64_t)split * pb / ps);
+    blk_end = split == ps ? nb : (int)((int64_t)(split + 1) * pb / ps);
+  } else {
+    blk_begin = (int)((int64_t)split * nb / n_splits);
+    blk_end = (int)((int64_t)(split + 1) * nb / n_splits);
+  }
 
   // Q tile of this head -> LDS (rows padded by 16 B: the 16 B-per-lane operand reads below are bank-conflict
   // free).  The region is reused by the wave merge after the key loop.
@@ -118,29 +138,34 @@ __global__ void __launch_bounds__(256)
     const int row = threadIdx.x >> 2, seg = threadIdx.x & 3;
     const int64_t grow = (int64_t)b * kTQ + row;
     const float* cs_row = cs + grow * kHD;  // 64 pairs x 2
-    float lo[16], hi[16];
-    qkv_gather(qkv, grow, h * kHD, seg, lo, hi);
-    rope16(cs_row, seg, lo, hi);
     uint8_t* qrow = q_lds + row * kQRow;
-    *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack_bf16x8(lo);
-    *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack_bf16x8(lo + 8);
-    *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack_bf16x8(hi);
-    *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack_bf16x8(hi + 8);
-    if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
-      const int slot = S + row;
-      qkv_gather(qkv, grow, d + h * kHD, seg, lo, hi);
+    auto stage_q = [&](float (&lo)[16], float (&hi)[16]) {
       rope16(cs_row, seg, lo, hi);
+      *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack_bf16x8(lo);
+      *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack_bf16x8(lo + 8);
+      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack_bf16x8(hi);
+      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack_bf16x8(hi + 8);
+    };
+    if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
+      float lo[3][16], hi[3][16];
+      qkv_gather<3>(qkv, grow, h * kHD, d, seg, lo, hi);
+      stage_q(lo[0], hi[0]);
+      const int slot = S + row;
+      rope16(cs_row, seg, lo[1], hi[1]);
       // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg)) = pack_bf16x8(lo);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg + 8)) = pack_bf16x8(lo + 8);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg)) = pack_bf16x8(hi);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi + 8);
-      qkv_gather(qkv, grow, 2 * d + h * kHD, seg, lo, hi);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg)) = pack_bf16x8(lo[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg + 8)) = pack_bf16x8(lo[1] + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg)) = pack_bf16x8(hi[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi[1] + 8);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        vc[v_index(g, layer, b, h, slot, 16 * seg + i)] = float_to_bf16(lo[i]);
-        vc[v_index(g, layer, b, h, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[i]);
+        vc[v_index(g, layer, b, h, slot, 16 * seg + i)] = float_to_bf16(lo[2][i]);
+        vc[v_index(g, layer, b, h, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[2][i]);
       }
+    } else {
+      float lo[1][16], hi[1][16];
+      qkv_gather<1>(qkv, grow, h * kHD, d, seg, lo, hi);
+      stage_q(lo[0], hi[0]);
     }
   }
   __syncthreads();  // Q tile complete; the tree rows written above are complete (stores drain before a barrier)
@@ -286,7 +311,8 @@ __global__ void __launch_bounds__(256)
       }
   }
   __syncthreads();
-  const int qq = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 32;
+  // thread (qq = t/4, s = t%4) merges features 16*jj + 4*s + e (jj < 8, e < 4) of query qq
+  const int qq = threadIdx.x >> 2, s4 = (threadIdx.x & 3) * 4;
   float mw[4], M = -INFINITY;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
@@ -303,24 +329,28 @@ __global__ void __launch_bounds__(256)
   float acc[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
+    const int f = 16 * (j >> 2) + s4 + (j & 3);
     float a = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) a += wt[w] * o_lds[(w * kHD + seg + j) * kOPad + qq];
+    for (int w = 0; w < 4; ++w) a += wt[w] * o_lds[(w * kHD + f) * kOPad + qq];
     acc[j] = a;
   }
   if (n_splits == 1) {
     const float inv = 1.0f / L;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + seg);
+    bf16_t* dst = att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + s4;
 #pragma unroll
-    for (int j = 0; j < 32; j += 2) {
-      bf16_t lo = float_to_bf16(acc[j] * inv), hi = float_to_bf16(acc[j + 1] * inv);
-      dst[j >> 1] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
+    for (int jj = 0; jj < 8; ++jj) {
+      bf16_t v0 = float_to_bf16(acc[4 * jj] * inv), v1 = float_to_bf16(acc[4 * jj + 1] * inv);
+      bf16_t v2 = float_to_bf16(acc[4 * jj + 2] * inv), v3 = float_to_bf16(acc[4 * jj + 3] * inv);
+      *reinterpret_cast<uint2*>(dst + 16 * jj) =
+          uint2{(uint32_t)v0.bits | ((uint32_t)v1.bits << 16), (uint32_t)v2.bits | ((uint32_t)v3.bits << 16)};
     }
   } else {
     const int64_t pidx = ((int64_t)(b * g.n_heads + h) * n_splits + split);
-    float* po = part_o + (pidx * kTQ + qq) * kHD + seg;
+    float* po = part_o + (pidx * kTQ + qq) * kHD + s4;
 #pragma unroll
-    for (int j = 0; j < 32; ++j) po[j] = acc[j];
+    for (int jj = 0; jj < 8; ++jj)
+      *reinterpret_cast<float4*>(po + 16 * jj) = float4{acc[4 * jj], acc[4 * jj + 1], acc[4 * jj + 2], acc[4 * jj + 3]};
     if ((threadIdx.x & 3) == 0) {
       part_ml[(pidx * 2 + 0) * kTQ + qq] = M;
       part_ml[(pidx * 2 + 1) * kTQ + qq] = L;
@@ -328,52 +358,60 @@ __global__ void __launch_bounds__(256)
   }
 }
 
-// Merges the key-splits of one (sequence, head): fixed order, exact same weighting rule as above.
+// Merges the key-splits of 16 queries of one (sequence, head): fixed order, exact same weighting rule as above.
+// Thread (q = t/16, c = t%16) owns features 8c .. 8c+7 of query 16*blockIdx.z + q.
 __global__ void __launch_bounds__(256)
     attn_combine_kernel(int n_heads, int n_splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
                         bf16_t* __restrict__ att_out) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int d = n_heads * kHD;
-  const int qq = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 32;
+  const int qq = blockIdx.z * 16 + (threadIdx.x >> 4), f0 = (threadIdx.x & 15) * 8;
   const int64_t p0 = (int64_t)(b * n_heads + h) * n_splits;
   float M = -INFINITY;
   for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((p0 + s) * 2 + 0) * kTQ + qq]);
   float L = 0.f;
-  float acc[32];
+  float acc[8];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) acc[j] = 0.f;
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
   for (int s = 0; s < n_splits; ++s) {
-    float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
+    const float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
     L += w * part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
-    const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + seg);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float4 v = po[j];
-      acc[4 * j] += w * v.x;
-      acc[4 * j + 1] += w * v.y;
-      acc[4 * j + 2] += w * v.z;
-      acc[4 * j + 3] += w * v.w;
-    }
+    const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
+    const float4 v0 = po[0], v1 = po[1];
+    acc[0] += w * v0.x, acc[1] += w * v0.y, acc[2] += w * v0.z, acc[3] += w * v0.w;
+    acc[4] += w * v1.x, acc[5] += w * v1.y, acc[6] += w * v1.z, acc[7] += w * v1.w;
   }
   const float inv = 1.0f / L;
-  uint32_t* dst = reinterpret_cast<uint32_t*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + seg);
+  uint32_t pk[4];
 #pragma unroll
-  for (int j = 0; j < 32; j += 2) {
-    bf16_t lo = float_to_bf16(acc[j] * inv), hi = float_to_bf16(acc[j + 1] * inv);
-    dst[j >> 1] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
+  for (int j = 0; j < 4; ++j) {
+    bf16_t lo = float_to_bf16(acc[2 * j] * inv), hi = float_to_bf16(acc[2 * j + 1] * inv);
+    pk[j] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
   }
+  *reinterpret_cast<u32x4*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + f0) = u32x4{pk[0], pk[1], pk[2], pk[3]};
 }
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
   return dtype == MDZ_BF16 && g.tiled && g.head_dim == kHD && host_tree(tree)->T == kTQ;
 }
 
-static int attn_splits(int B, int n_heads, int max_prefix) {
+// Key-splits per (sequence, head).  fused: the kernel starts from the QKV partial sums, so one split is the tree
+// split and the rest share the prefix: as many as keep every workgroup resident at once (one per CU: the merge
+// buffer takes most of a CU's LDS), but no more than one per four prefix blocks (one block per wave).
+static int attn_splits(int B, int n_heads, int max_prefix, bool fused) {
   static const char* env = getenv("MDZ_ATTN_SPLITS");  // development knob
-  if (env && atoi(env) > 0) return atoi(env);
+  if (env && atoi(env) > 0) return atoi(env) > 32 ? 32 : atoi(env);
+  const int pairs = B * n_heads;
+  if (fused) {
+    int ps = 256 / pairs - 1;
+    const int by_len = (max_prefix >> 5) / 4;
+    if (ps > by_len) ps = by_len;
+    if (ps > 31) ps = 31;
+    return ps >= 1 ? ps + 1 : 1;
+  }
   int nb = (max_prefix + kTQ + 31) / 32;
-  int by_len = nb / 8;                               // >= 2 blocks per wave
-  int by_fill = (512 + B * n_heads - 1) / (B * n_heads);  // aim at ~512 workgroups
+  int by_len = nb / 8;                        // >= 2 blocks per wave
+  int by_fill = (512 + pairs - 1) / pairs;    // aim at ~512 workgroups
   int s = by_len < by_fill ? by_len : by_fill;
   if (s > 32) s = 32;
   if (s < 1) s = 1;
@@ -381,7 +419,8 @@ static int attn_splits(int B, int n_heads, int max_prefix) {
 }
 
 int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
-  int s = attn_splits(B, n_heads, max_prefix);
+  int s = attn_splits(B, n_heads, max_prefix, true), s2 = attn_splits(B, n_heads, max_prefix, false);
+  s = s > s2 ? s : s2;
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
 }
 
@@ -396,19 +435,19 @@ int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const fl
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
     attr_set = true;
   }
-  const int splits = attn_splits(B, g.n_heads, max_prefix);
+  const int splits = attn_splits(B, g.n_heads, max_prefix, qkv != nullptr);
   MDZ_REQUIRE(scratch_bytes >= attn_mfma_scratch_bytes(B, g.n_heads, max_prefix), MDZ_EWORKSPACE,
               "attention: scratch too small");
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kTQ * kHD;
   dim3 grid(splits, g.n_heads, B);
-  const Partials none{nullptr, 0, 0, 0, nullptr, 1};
+  const Partials none = single_slot(nullptr, 0, 0);
   attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, qkv ? *qkv : none, cs, g, (bf16_t*)kc,
                                                           (bf16_t*)vc, layer, seq_len, max_prefix, (bf16_t*)att_out,
                                                           part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_combine_kernel<<<dim3(g.n_heads, B), 256, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
+    attn_combine_kernel<<<dim3(g.n_heads, B, kTQ / 16), 256, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;

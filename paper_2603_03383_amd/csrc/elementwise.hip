@@ -258,7 +258,7 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   dim3 grid(B * t->T, g.n_heads);
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
   if (dtype == MDZ_BF16 && g.tiled && g.head_dim == 128 && g.n_heads % 4 == 0 && qkv.n <= kMaxSlots &&
-      qkv.stride % 4 == 0 && (qkv.counts == nullptr || qkv.band_cols % 128 == 0))
+      qkv.stride % 4 == 0 && (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
     rope_kvwrite_vec_kernel<<<dim3(B * t->T, g.n_heads / 4), 192, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc,
                                                                           (bf16_t*)vc, layer, seq_len, max_prefix);
   else if (dtype == MDZ_BF16)
@@ -322,7 +322,7 @@ int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStrea
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
   // gate and up tiles of a pair lie in the same band (band widths are multiples of 64), so one count serves both
-  if (dtype == MDZ_BF16 && F % 32 == 0 && gu.n <= kMaxSlots && gu.stride % 4 == 0 && (gu.counts == nullptr || gu.band_cols % 64 == 0))
+  if (dtype == MDZ_BF16 && F % 32 == 0 && gu.n <= kMaxSlots && gu.stride % 4 == 0 && (gu.split_grid == 0 || gu.band_cols % 64 == 0))
     swiglu_vec_kernel<<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(gu, (bf16_t*)u, M, F);
   else if (dtype == MDZ_BF16)
     swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);

@@ -23,14 +23,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// owner of flat unit u when U units are cut into G ranges [floor(w*U/G), floor((w+1)*U/G))
-__host__ __device__ inline int64_t range_owner(int64_t u, int64_t U, int64_t G) { return ((u + 1) * G - 1) / U; }
-
 template <int WPB, int NT, int MT, int CK>
 __global__ void __launch_bounds__(WPB * 64)
     gemm_mfma_kernel(const bf16_t* __restrict__ X, int M, int K, const bf16_t* __restrict__ Wp, int n_tiles,
-                     int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride,
-                     int32_t* __restrict__ counts, int whole_bands) {
+                     int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride, int whole_bands) {
   constexpr int ROWS = MT * 32;
   constexpr int KH = CK / 32;                       // MFMA k-steps per half stage
   constexpr int LROW = CK * 2 + 16;                 // bytes per staged X row (16 B pad)
@@ -39,10 +35,10 @@ __global__ void __launch_bounds__(WPB * 64)
   uint8_t(*lds)[ROWS * LROW] = reinterpret_cast<uint8_t(*)[ROWS * LROW]>(lds_raw);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t G = gridDim.x, w = blockIdx.x;
-  const int bands = (n_tiles + WPB * NT - 1) / (WPB * NT);
-  const int64_t U = (int64_t)bands * n_stages;
-  int u_lo, u_hi;  // flat unit range of this workgroup (U < 2^31: checked on the host)
+  const uint32_t G = gridDim.x, w = blockIdx.x;
+  const uint32_t bands = (n_tiles + WPB * NT - 1) / (WPB * NT);
+  const uint32_t U = bands * n_stages;
+  int u_lo, u_hi;  // flat unit range of this workgroup (U * G < 2^31: checked on the host)
   if (whole_bands) {
     u_lo = (int)(w * bands / G) * n_stages;
     u_hi = (int)((w + 1) * bands / G) * n_stages;
@@ -138,15 +134,8 @@ __global__ void __launch_bounds__(WPB * 64)
   // D layout of the 32x32 MFMA: lane holds column (lane % 32); register r is row 8*(r/4) + 4*(lane/32) + r%4.
   auto flush = [&]() {
     const int b = cb;
-    int slot = 0;
-    if (!whole_bands) {
-      const int64_t first_owner = range_owner((int64_t)b * n_stages, U, G);
-      slot = (int)(w - first_owner);
-      if (counts && threadIdx.x == 0 && slot == 0)
-        counts[b] = (int)(range_owner((int64_t)(b + 1) * n_stages - 1, U, G) - first_owner + 1);
-    } else if (counts && threadIdx.x == 0) {
-      counts[b] = 1;
-    }
+    // slot = this workgroup's rank among the ranges that touch the band (see Partials::count)
+    const int slot = whole_bands ? 0 : (int)(w - Partials::owner((uint32_t)b * n_stages, U, G));
     float* out = P + (int64_t)slot * part_stride;
     const int col = lane & 31, rbase = (lane >> 5) * 4;
     // 32-bit element offsets (the host checks M * ldp < 2^31).  The empty asm makes the row pitch opaque here,
@@ -277,22 +266,24 @@ bool gemm_mfma_supported(int dtype, int M, int N, int K) {
   return dtype == MDZ_BF16 && M >= 1 && M <= 64 && N % 32 == 0 && K % 128 == 0 && K >= 128;
 }
 
-int gemm_mfma_band_cols(int M, int N, int K, int max_split) {
-  GemmPlan p = plan_gemm(M, N, K, max_split);
-  return p.wpb * p.nt * 32;
-}
-
-// Writes partial sums into slots of P (slot s at P + s*part_stride, each [M][ldp] fp32).  counts[band] receives
-// the number of slots written for each band of `*band_cols` columns (1 everywhere when max_split <= 1).
+// Writes partial sums into slots of P (slot s at P + s*part_stride, each [M][ldp] fp32) and fills the fields of
+// *res that describe how many slots each band of columns received (one everywhere when max_split <= 1).
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                     int max_split, int32_t* counts, int* band_cols, hipStream_t st) {
+                     int max_split, Partials* res, hipStream_t st) {
   GemmPlan p = plan_gemm(M, N, K, max_split);
   ProfScope prof_(p.mt == 2 ? (p.wpb == 4 ? PROF_GEMM_W64 : PROF_GEMM_N64) : (p.wpb == 4 ? PROF_GEMM_W32 : PROF_GEMM_N32),
                   st);
   const int n_tiles = N / 32, n_stages = K / p.ck;
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
-  *band_cols = p.wpb * p.nt * 32;
+  const int bands = (n_tiles + p.wpb * p.nt - 1) / (p.wpb * p.nt);
+  MDZ_REQUIRE((int64_t)bands * n_stages * p.grid < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: %d x %d units on %d workgroups overflow",
+              bands, n_stages, p.grid);
+  res->band_cols = p.wpb * p.nt * 32;
+  res->n_stages = n_stages;
+  res->split_units = (uint32_t)bands * n_stages;
+  res->split_grid = p.whole ? 0 : (uint32_t)p.grid;
+  res->n = p.whole ? 1 : max_split;
   const bf16_t* x = (const bf16_t*)X;
   const bf16_t* w = (const bf16_t*)Wp;
 #define MDZ_GEMM_CASE(WPB, NT, MT, CK)                                                                       \
@@ -305,7 +296,7 @@ int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int 
       attr_set = true;                                                                                       \
     }                                                                                                        \
     gemm_mfma_kernel<WPB, NT, MT, CK><<<p.grid, WPB * 64, lds_bytes, st>>>(x, M, K, w, n_tiles, n_stages, P, \
-                                                                           ldp, part_stride, counts, p.whole); \
+                                                                           ldp, part_stride, p.whole);         \
   } else
   MDZ_GEMM_CASE(4, 1, 2, 128)
   MDZ_GEMM_CASE(4, 1, 1, 128)

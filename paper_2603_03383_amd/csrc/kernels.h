@@ -7,17 +7,30 @@
 namespace mdz {
 
 // Output of a GEMM: partial-sum slots, each [M][ld] fp32, `stride` elements apart.  The consumer adds slots
-// 0..count-1 in that fixed order (results do not depend on scheduling); count is `n` for every column when
-// counts == NULL, else counts[column / band_cols].
+// 0..count-1 in that fixed order (results do not depend on scheduling).  count is `n` for every column when
+// split_grid == 0.  Otherwise the GEMM cut its U = bands * n_stages (band, K-stage) units, numbered band-major,
+// into split_grid equal contiguous ranges, range w = [floor(w*U/G), floor((w+1)*U/G)), and every range that
+// touches a band wrote one slot of it: the count of a band follows from that arithmetic alone, so consumers
+// need no table (and no dependent memory read) to know it.
 struct Partials {
   const float* p;
-  int n;
+  int n;  // slot count when split_grid == 0, else an upper bound
   int64_t stride;
   int64_t ld;
-  const int32_t* counts;
-  int band_cols;
-  __host__ __device__ inline int count(int col) const { return counts ? counts[col / band_cols] : n; }
+  int band_cols;             // columns per band
+  int n_stages;              // K-stages per band
+  uint32_t split_units;      // U
+  uint32_t split_grid;       // G (0: every column has n slots)
+  // owner of unit u: the range w with floor(w*U/G) <= u < floor((w+1)*U/G); U * G < 2^31 (checked by the GEMM)
+  __host__ __device__ static inline uint32_t owner(uint32_t u, uint32_t U, uint32_t G) { return ((u + 1) * G - 1) / U; }
+  __host__ __device__ inline int count(int col) const {
+    if (split_grid == 0) return n;
+    const uint32_t band = (uint32_t)col / (uint32_t)band_cols;
+    return (int)(owner((band + 1) * n_stages - 1, split_units, split_grid) -
+                 owner(band * n_stages, split_units, split_grid)) + 1;
+  }
 };
+inline Partials single_slot(const float* p, int64_t stride, int64_t ld) { return Partials{p, p ? 1 : 0, stride, ld, 1, 1, 0, 0}; }
 
 // ---- layout movers (layout.hip) ------------------------------------------------------------------
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
@@ -73,9 +86,8 @@ int launch_accept(int tree, const int32_t* tree_tokens, const int32_t* node_argm
 // ---- GEMM: sum_k X[m][k] * W[n][k], W packed, X storage dtype [M][K] ------------------------------
 // Writes at most max_split partial sums into `out` (partial s at out + s*M*ld, leading dimension ld) and
 // describes them in *res.  max_split == 1 yields the finished product in out.
-// counts: device scratch of N/32 + 1 ints that receives per-band slot counts when max_split > 1.
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld,
-                int max_split, int32_t* counts, Partials* res, hipStream_t st);
+                int max_split, Partials* res, hipStream_t st);
 
 // ---- tree-masked attention --------------------------------------------------------------------------
 // q [B*T][d] storage dtype (rotated); att_out [B*T][d] storage dtype

@@ -24,28 +24,19 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K);
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                     int max_split, int32_t* counts, int* band_cols, hipStream_t st);
+                     int max_split, Partials* res, hipStream_t st);
 
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld, int max_split,
-                int32_t* counts, Partials* res, hipStream_t st) {
-  res->p = out;
-  res->n = 1;
-  res->stride = (int64_t)M * ld;
-  res->ld = ld;
-  res->counts = nullptr;
-  res->band_cols = 1;
+                Partials* res, hipStream_t st) {
+  *res = single_slot(out, (int64_t)M * ld, ld);
   const int rows_per_launch = M <= 64 ? M : 64;
   if (gemm_mfma_supported(dtype, rows_per_launch, N, K) && (M <= 64 || M % 64 == 0)) {
-    if (max_split > 1) {
-      res->counts = counts;
-      res->n = max_split;  // upper bound; the per-band counts decide
-    }
     // More than 64 rows (several sequences): one launch per block of 64 rows.  Every launch uses the same plan, so
     // the slot counts are identical; the first launch streams the matrix from HBM, the following ones mostly from
     // the memory-side cache.
     for (int m0 = 0; m0 < M; m0 += rows_per_launch) {
       int rc = launch_gemm_mfma((const char*)X + (int64_t)m0 * K * 2, Wp, out + (int64_t)m0 * ld, rows_per_launch, N, K, ld,
-                                res->stride, max_split, max_split > 1 ? counts : nullptr, &res->band_cols, st);
+                                res->stride, max_split, res, st);
       if (rc) return rc;
     }
     return MDZ_OK;
@@ -82,7 +73,7 @@ int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float*
                           void* scratch, int64_t scratch_bytes, hipStream_t st) {
   static const bool unfused = getenv("MDZ_UNFUSED_ROPE") != nullptr;  // development knob
   if (!unfused && attn_mfma_supported(dtype, tree, g) && qkv.stride % 4 == 0 && qkv.ld % 4 == 0 &&
-      (qkv.counts == nullptr || qkv.band_cols % 128 == 0))
+      (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
     return launch_attention_mfma(tree, nullptr, &qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
                                  scratch_bytes, st);
   int rc = launch_rope_kvwrite(dtype, tree, qkv, cs, q_scratch, g, kc, vc, layer, seq_len, B, max_prefix, st);
@@ -93,7 +84,7 @@ int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float*
 
 // ---- workspace ------------------------------------------------------------------------------------
 struct Workspace {
-  int64_t rope_cs, x, xn, part, counts, q, att, u, logits, h, z, hlogits, sel, sel_bytes, attn_scratch, total;
+  int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, sel, sel_bytes, attn_scratch, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~int64_t(255); }
@@ -117,8 +108,6 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
     int64_t layer_part = max_split_for((int)rows) * rows * widest * 4;
     int64_t head_part = max_split_for(B) * (int64_t)B * m.d * 4;
     w.part = take(layer_part > head_part ? layer_part : head_part);
-    int64_t widest_n = widest > m.vocab ? widest : m.vocab;
-    w.counts = take((widest_n / 32 + 1) * 4);  // per-band slot counts of the last GEMM
   }
   w.q = take(rows * m.d * es);
   w.att = take(rows * m.d * es);
@@ -188,20 +177,19 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   float* cs = (float*)(ws + w.rope_cs);
   void* xn = ws + w.xn;
   float* part = (float*)(ws + w.part);
-  int32_t* cnt = (int32_t*)(ws + w.counts);
   void* q = ws + w.q;
   void* att = ws + w.att;
   void* u = ws + w.u;
   Partials pr;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, 3 * m.d, m.d, 3 * m.d, ms, cnt, &pr, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, 3 * m.d, m.d, 3 * m.d, ms, &pr, st))) return rc;
   if ((rc = launch_rope_attention(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
                                   ws + w.attn_scratch, w.total - w.attn_scratch, st)))
     return rc;
-  if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, cnt, &pr, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, &pr, st))) return rc;
   if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, cnt, &pr, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
   if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, cnt, &pr, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, &pr, st))) return rc;
   return launch_residual_rmsnorm(m.dtype, x, pr, g_next, xn_next, rows, m.d, m.rms_eps, st);
 }
 
@@ -339,16 +327,16 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   if (root_token) {
     if ((rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
   } else {
-    if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, nullptr, &pr, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, wsb + L.sel, L.sel_bytes, st))) return rc;
   }
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
     const void* b1 = w->head_b1 ? w->head_b1[k] : nullptr;
-    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part, B, m.d, m.d, m.d, max_split_for(B), (int32_t*)(wsb + L.counts), &pr, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part, B, m.d, m.d, m.d, max_split_for(B), &pr, st))) return rc;
     if ((rc = launch_head_residual(m.dtype, h, pr, b1, z, B, m.d, st))) return rc;
     float* lk = hl + (int64_t)(k + 1) * V;
-    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, nullptr, &pr, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, wsb + L.sel, L.sel_bytes, st)))
       return rc;
     seg += t->caps[k];
@@ -378,7 +366,7 @@ int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, 
                               (float*)((char*)ws + L.rope_cs), st)))
     return rc;
   const int rows = B * t->T;
-  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, Partials{nullptr, 0, 0, 0, nullptr, 1}, lw->g_attn, (char*)ws + L.xn, rows,
+  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, single_slot(nullptr, 0, 0), lw->g_attn, (char*)ws + L.xn, rows,
                                     model->d, model->rms_eps, st)))
     return rc;
   return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, nullptr, nullptr, st);
@@ -411,7 +399,7 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   if ((rc = launch_embed(m.dtype, w->embed, tree_tokens, x, rows, m.d, m.vocab, st))) return rc;
   void* xn = wsb + L.xn;
   void* hid = hidden_out ? hidden_out : xn;
-  if ((rc = launch_residual_rmsnorm(m.dtype, x, Partials{nullptr, 0, 0, 0, nullptr, 1}, w->layers[0].g_attn, xn, rows, m.d,
+  if ((rc = launch_residual_rmsnorm(m.dtype, x, single_slot(nullptr, 0, 0), w->layers[0].g_attn, xn, rows, m.d,
                                     m.rms_eps, st)))
     return rc;
   for (int l = 0; l < m.n_layers; ++l) {
@@ -422,7 +410,7 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   }
   float* logits = logits_opt ? logits_opt : (float*)(wsb + L.logits);
   Partials pr;
-  if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, 1, nullptr, &pr, st))) return rc;
+  if ((rc = launch_gemm(m.dtype, hid, w->lm_head, logits, rows, m.vocab, m.d, m.vocab, 1, &pr, st))) return rc;
   return launch_argmax(logits, rows, m.vocab, m.vocab, node_argmax, wsb + L.sel, L.sel_bytes, st);
 }
 
