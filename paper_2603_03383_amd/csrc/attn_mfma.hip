@@ -396,15 +396,16 @@ bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
 }
 
 // Key-splits per (sequence, head).  fused: the kernel starts from the QKV partial sums, so one split is the tree
-// split and the rest share the prefix: as many as keep every workgroup resident at once (one per CU: the merge
-// buffer takes most of a CU's LDS), but no more than one per four prefix blocks (one block per wave).
+// split and the rest share the prefix: at most as many as keep every workgroup resident at once (one per CU: the
+// merge buffer takes most of a CU's LDS), and one per ten prefix blocks: the tree split's reduce-write-read
+// chain lasts about as long as ten blocks of a prefix split, and more workgroups only slow every reduce down.
 static int attn_splits(int B, int n_heads, int max_prefix, bool fused) {
   static const char* env = getenv("MDZ_ATTN_SPLITS");  // development knob
   if (env && atoi(env) > 0) return atoi(env) > 32 ? 32 : atoi(env);
   const int pairs = B * n_heads;
   if (fused) {
     int ps = 256 / pairs - 1;
-    const int by_len = (max_prefix >> 5) / 4;
+    const int by_len = ((max_prefix >> 5) + 5) / 10;
     if (ps > by_len) ps = by_len;
     if (ps > 31) ps = 31;
     return ps >= 1 ? ps + 1 : 1;
