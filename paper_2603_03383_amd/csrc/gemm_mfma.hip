@@ -218,6 +218,7 @@ __global__ void __launch_bounds__(WPB * 64)
 
 struct GemmPlan {
   int wpb, nt, mt, ck, grid, whole;
+  int slots;  // most partial-sum slots any band receives
 };
 
 constexpr int kNumCU = 256;
@@ -246,21 +247,30 @@ static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
   const int bands = (n_tiles + p.wpb * p.nt - 1) / (p.wpb * p.nt);
   const int n_stages = K / p.ck;
   const int64_t U = (int64_t)bands * n_stages;
+  p.slots = 1;
   if (p.whole) {
     if (p.grid > bands) p.grid = bands;
   } else {
     if (p.grid > U) p.grid = (int)U;
-    // a band may be shared by at most max_split writers: ceil(n_stages / floor(U/grid)) + 1 <= max_split
-    while (p.grid > 1) {
-      int64_t per = U / p.grid;
-      int64_t writers = (n_stages + per - 1) / per + 1;
-      if (writers <= max_split) break;
-      p.grid = p.grid * 3 / 4;
-    }
+    // the most ranges that touch one band (exact, by the ownership rule of Partials) must fit max_split slots
+    auto most_writers = [&](int grid) {
+      uint32_t most = 0;
+      for (int b = 0; b < bands; ++b) {
+        uint32_t n = Partials::owner((uint32_t)(b + 1) * n_stages - 1, (uint32_t)U, grid) -
+                     Partials::owner((uint32_t)b * n_stages, (uint32_t)U, grid) + 1;
+        most = n > most ? n : most;
+      }
+      return (int)most;
+    };
+    while (p.grid > 1 && (U * p.grid >= (int64_t)1 << 31 || (p.slots = most_writers(p.grid)) > max_split)) p.grid = p.grid * 7 / 8;
+    if (p.grid <= 1) p.slots = 1;
   }
   if (p.grid < 1) p.grid = 1;
   return p;
 }
+
+// most partial-sum slots per band that launch_gemm_mfma will use for this problem (sizes the slot workspace)
+int gemm_mfma_slots(int M, int N, int K, int max_split) { return plan_gemm(M, N, K, max_split).slots; }
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K) {
   return dtype == MDZ_BF16 && M >= 1 && M <= 64 && N % 32 == 0 && K % 128 == 0 && K >= 128;
@@ -283,7 +293,7 @@ int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int 
   res->n_stages = n_stages;
   res->split_units = (uint32_t)bands * n_stages;
   res->split_grid = p.whole ? 0 : (uint32_t)p.grid;
-  res->n = p.whole ? 1 : max_split;
+  res->n = p.slots;
   const bf16_t* x = (const bf16_t*)X;
   const bf16_t* w = (const bf16_t*)Wp;
 #define MDZ_GEMM_CASE(WPB, NT, MT, CK)                                                                       \

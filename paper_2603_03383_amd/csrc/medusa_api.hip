@@ -23,6 +23,7 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
                              hipStream_t st);
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K);
+int gemm_mfma_slots(int M, int N, int K, int max_split);
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
                      int max_split, Partials* res, hipStream_t st);
 
@@ -45,7 +46,15 @@ int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int
 }
 
 // split-K is only worth its partial-sum traffic for skinny problems
-static int max_split_for(int rows) { return (rows <= 64 || rows % 64 == 0) ? 8 : 1; }
+static int max_split_for(int rows) { return (rows <= 64 || rows % 64 == 0) ? 12 : 1; }
+// fp32 elements of partial-sum workspace a [rows, N] = [rows, K] x [N, K] GEMM needs
+static int64_t gemm_part_elems(int dtype, int rows, int N, int K) {
+  const int per = rows <= 64 ? rows : 64;
+  const int slots = (gemm_mfma_supported(dtype, per, N, K) && (rows <= 64 || rows % 64 == 0))
+                        ? gemm_mfma_slots(per, N, K, max_split_for(rows))
+                        : 1;
+  return (int64_t)slots * rows * N;
+}
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g);
 int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix);
@@ -104,9 +113,13 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.x = take(rows * m.d * 4);
   w.xn = take(rows * m.d * es);
   {
-    int64_t widest = 3 * (int64_t)m.d > 2 * (int64_t)m.ffn ? 3 * (int64_t)m.d : 2 * (int64_t)m.ffn;
-    int64_t layer_part = max_split_for((int)rows) * rows * widest * 4;
-    int64_t head_part = max_split_for(B) * (int64_t)B * m.d * 4;
+    int64_t layer_part = 0;
+    const int shapes[4][2] = {{3 * m.d, m.d}, {m.d, m.d}, {2 * m.ffn, m.d}, {m.d, m.ffn}};
+    for (auto& sh : shapes) {
+      int64_t e = gemm_part_elems(m.dtype, (int)rows, sh[0], sh[1]) * 4;
+      layer_part = e > layer_part ? e : layer_part;
+    }
+    int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d) * 4;
     w.part = take(layer_part > head_part ? layer_part : head_part);
   }
   w.q = take(rows * m.d * es);
