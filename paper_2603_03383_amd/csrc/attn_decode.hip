@@ -1,0 +1,195 @@
+// Single-query attention over the tiled bf16 KV cache: the degenerate tree of one node, i.e. one ordinary
+// autoregressive decode step (Section 4.1: the Time_AR that the paper's Overhead and Speedup are measured
+// against).  The node sees the prefix and itself, so the mask is "slot <= S".
+//
+// One workgroup = 4 waves handles one (sequence, head, key-split); a wave walks 32-key blocks of the tiled cache
+// (common.h) with the same contiguous 16-byte-per-lane loads as the tree kernel.  There is one query, so the
+// products are plain FMAs: in a K unit lane l holds 8 features of key l % 32, and the two half-waves hold the two
+// halves of every 16-feature step, so a score is a 64-term sum per lane plus one exchange with lane ^ 32.  In a V
+// unit lane l holds feature 32t + l % 32 for 8 keys; their probabilities come from the lanes that own those keys.
+// Waves merge through LDS, key-splits through a second small kernel, both in a fixed order.
+#include "kernels.h"
+
+namespace mdz {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+constexpr int kHD = 128;
+
+__device__ inline float fast_exp2_attn(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float half_max(float v) {  // max over the 32 lanes of a half-wave (both halves hold the same set)
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline float half_sum(float v) {
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline void unpack8(u32x4 v, float (&f)[8]) {
+  f[0] = __uint_as_float(v.x << 16), f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16), f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16), f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16), f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+}  // namespace
+
+__global__ void __launch_bounds__(256)
+    attn_decode_kernel(const bf16_t* __restrict__ q, KvGeom g, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                       int layer, const int32_t* __restrict__ seq_len, int max_prefix, bf16_t* __restrict__ att_out,
+                       float* __restrict__ part_o, float* __restrict__ part_ml) {
+  __shared__ float o_lds[4][kHD];
+  __shared__ float ml_lds[4][2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int key = lane & 31, half = lane >> 5;
+  const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y, b = blockIdx.z;
+  const int d = g.n_heads * kHD;
+  const int S = min(max(seq_len[b], 0), max_prefix);
+  const int n_slots = S + 1;  // the prefix and the node itself
+  const int nb = (n_slots + 31) >> 5;
+  const int blk_begin = (int)((int64_t)split * nb / n_splits), blk_end = (int)((int64_t)(split + 1) * nb / n_splits);
+
+  // the lane's 64 query features: 16*ks + 8*half + e, pre-scaled by log2(e) / sqrt(head_dim)
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
+  float qf[8][8];
+  const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)b * d + h * kHD);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    unpack8(qp[2 * ks + half], qf[ks]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[ks][e] *= scale_log2;
+  }
+
+  const int64_t head_base = kv_head_base(g, layer, b, h);
+  const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
+  const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  float o[4] = {0.f, 0.f, 0.f, 0.f};  // feature 32t + key, over the keys this half-wave owns
+  for (int blk = blk_begin + wave; blk < blk_end; blk += 4) {
+    u32x4 kd[8], vd[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kd[i] = kp[(int64_t)blk * 512 + i * 64];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vd[i] = vp[(int64_t)blk * 512 + i * 64];
+    float s = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      float kf[8];
+      unpack8(kd[ks], kf);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += qf[ks][e] * kf[e];
+    }
+    s += __shfl_xor(s, 32, 64);  // both half-waves now hold the score of key `key`
+    s = (blk * 32 + key < n_slots) ? s : -INFINITY;
+    const float m_new = fmaxf(m_run, half_max(s));  // finite: a block in range holds at least one visible slot
+    const float p = fast_exp2_attn(s - m_new);
+    const float alpha = fast_exp2_attn(m_run - m_new);
+    l_run = l_run * alpha + half_sum(p);
+    m_run = m_new;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) o[t] *= alpha;
+    // V unit (2t + s2): feature 32t + key, keys 16*s2 + 8*(e/4) + 4*half + e%4; the probability of key k lives in lane k
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      float pe[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pe[e] = __shfl(p, 16 * s2 + 8 * (e >> 2) + 4 * half + (e & 3), 64);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float vf[8];
+        unpack8(vd[2 * t + s2], vf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[t] += pe[e] * vf[e];
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) o[t] += __shfl_xor(o[t], 32, 64);  // the two half-waves own disjoint keys
+
+  // ---- merge the four waves (fixed order), then store or hand the partial result to the combine kernel
+  if (half == 0) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) o_lds[wave][32 * t + key] = o[t];
+    if (key == 0) ml_lds[wave][0] = m_run, ml_lds[wave][1] = l_run;
+  }
+  __syncthreads();
+  if (threadIdx.x < kHD) {
+    const int f = threadIdx.x;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, ml_lds[w][0]);
+    const float M_safe = M == -INFINITY ? 0.f : M;
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wt = fast_exp2_attn(ml_lds[w][0] - M_safe);
+      L += wt * ml_lds[w][1];
+      acc += wt * o_lds[w][f];
+    }
+    if (n_splits == 1) {
+      att_out[(int64_t)b * d + h * kHD + f] = float_to_bf16(acc / L);
+    } else {
+      const int64_t pidx = (int64_t)(b * g.n_heads + h) * n_splits + split;
+      part_o[pidx * kHD + f] = acc;
+      if (f == 0) part_ml[pidx * 2] = M, part_ml[pidx * 2 + 1] = L;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(128)
+    attn_decode_combine_kernel(int n_heads, int n_splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                               bf16_t* __restrict__ att_out) {
+  const int h = blockIdx.x, b = blockIdx.y, f = threadIdx.x;
+  const int64_t p0 = (int64_t)(b * n_heads + h) * n_splits;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(p0 + s) * 2]);
+  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float w = fast_exp2_attn(part_ml[(p0 + s) * 2] - M);
+    L += w * part_ml[(p0 + s) * 2 + 1];
+    acc += w * part_o[(p0 + s) * kHD + f];
+  }
+  att_out[((int64_t)b * n_heads + h) * kHD + f] = float_to_bf16(acc / L);
+}
+
+bool attn_decode_supported(int dtype, int tree, const KvGeom& g) {
+  return dtype == MDZ_BF16 && g.tiled && g.head_dim == kHD && host_tree(tree)->T == 1;
+}
+
+static int decode_splits(int B, int n_heads, int max_prefix) {
+  const int nb = (max_prefix + 1 + 31) / 32;
+  int by_len = nb / 4;                                     // >= one block per wave
+  int by_fill = (512 + B * n_heads - 1) / (B * n_heads);   // aim at ~512 workgroups
+  int s = by_len < by_fill ? by_len : by_fill;
+  return s > 32 ? 32 : s < 1 ? 1 : s;
+}
+
+int64_t attn_decode_scratch_bytes(int B, int n_heads, int max_prefix) {
+  const int s = decode_splits(B, n_heads, max_prefix);
+  return s == 1 ? 0 : (int64_t)B * n_heads * s * (kHD + 2) * 4;
+}
+
+int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                            const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                            int64_t scratch_bytes, hipStream_t st) {
+  ProfScope prof_(PROF_ATTN, st);
+  if (B == 0) return MDZ_OK;
+  const int splits = decode_splits(B, g.n_heads, max_prefix);
+  MDZ_REQUIRE(scratch_bytes >= attn_decode_scratch_bytes(B, g.n_heads, max_prefix), MDZ_EWORKSPACE,
+              "decode attention: scratch too small");
+  float* part_o = (float*)scratch;
+  float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kHD;
+  attn_decode_kernel<<<dim3(splits, g.n_heads, B), 256, 0, st>>>((const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
+                                                                 layer, seq_len, max_prefix, (bf16_t*)att_out, part_o, part_ml);
+  MDZ_LAUNCH_CHECK();
+  if (splits > 1) {
+    attn_decode_combine_kernel<<<dim3(g.n_heads, B), 128, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
+    MDZ_LAUNCH_CHECK();
+  }
+  return MDZ_OK;
+}
+
+}  // namespace mdz

@@ -62,13 +62,22 @@ int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const fl
                           void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                           void* scratch, int64_t scratch_bytes, hipStream_t st);
 
+bool attn_decode_supported(int dtype, int tree, const KvGeom& g);
+int64_t attn_decode_scratch_bytes(int B, int n_heads, int max_prefix);
+int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                            const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                            int64_t scratch_bytes, hipStream_t st);
+
 int64_t tree_attention_scratch_bytes(int dtype, int tree, const KvGeom& g, int B, int max_prefix) {
+  if (attn_decode_supported(dtype, tree, g)) return attn_decode_scratch_bytes(B, g.n_heads, max_prefix);
   return attn_mfma_supported(dtype, tree, g) ? attn_mfma_scratch_bytes(B, g.n_heads, max_prefix) : 0;
 }
 
 int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
                           int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                           int64_t scratch_bytes, hipStream_t st) {
+  if (attn_decode_supported(dtype, tree, g))
+    return launch_attention_decode(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch, scratch_bytes, st);
   if (attn_mfma_supported(dtype, tree, g))
     return launch_attention_mfma(tree, q, nullptr, nullptr, g, (void*)kc, (void*)vc, layer, seq_len, B, max_prefix,
                                  att_out, scratch, scratch_bytes, st);
@@ -318,7 +327,7 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   MDZ_REQUIRE(B >= 0 && Tsrc >= 1, MDZ_EINVAL, "medusa_heads: B %d, Tsrc %d", B, Tsrc);
   MDZ_REQUIRE(w->n_medusa == t->K, MDZ_ESHAPE, "medusa_heads: %d heads given, the tree has depth %d", w->n_medusa,
               t->K);
-  MDZ_REQUIRE(w->head_w1 && w->head_lm, MDZ_EINVAL, "medusa_heads: head weight arrays NULL");
+  MDZ_REQUIRE(t->K == 0 || (w->head_w1 && w->head_lm), MDZ_EINVAL, "medusa_heads: head weight arrays NULL");
   for (int k = 0; k < t->K; ++k)
     MDZ_REQUIRE(w->head_w1[k] && w->head_lm[k], MDZ_EINVAL, "medusa_heads: head %d weights NULL", k);
   MDZ_REQUIRE(root_token || w->lm_head, MDZ_EINVAL, "medusa_heads: need root_token or the base lm_head");

@@ -78,14 +78,18 @@ constexpr TreeTables make_tree(TreeRule rule) {
 
 constexpr TreeTables kTree15 = make_tree(TreeRule{3, {2, 2, 2, 0}, {2, 4, 8, 0}});
 constexpr TreeTables kTree64 = make_tree(TreeRule{4, {10, 10, 4, 4}, {10, 12, 4, 3}});
+// The degenerate tree: the root alone (no Medusa head).  A verify step over it is one ordinary autoregressive
+// decode step, the baseline the paper's Overhead and Speedup metrics are defined against (Section 4.1).
+constexpr TreeTables kTree1 = make_tree(TreeRule{0, {0, 0, 0, 0}, {0, 0, 0, 0}});
 
 static_assert(kTree15.T == 15 && kTree15.n_paths == 8 && kTree15.n_cand == 7, "15-node tree");
 static_assert(kTree64.T == 64 && kTree64.n_paths == 38 && kTree64.n_cand == 29, "64-node tree");
+static_assert(kTree1.T == 1 && kTree1.n_paths == 1 && kTree1.n_cand == 1 && kTree1.retrieve[0][0] == 0, "single node");
 
-constexpr int kNumTrees = 2;
+constexpr int kNumTrees = 3;
 
 inline const TreeTables* host_tree(int id) {
-  return id == 0 ? &kTree15 : id == 1 ? &kTree64 : nullptr;
+  return id == 0 ? &kTree15 : id == 1 ? &kTree64 : id == 2 ? &kTree1 : nullptr;
 }
 
 }  // namespace mdz

@@ -31,7 +31,8 @@ def test_header_symbols_are_exported():
         assert hasattr(lib, name), name
 
 
-@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64)], ids=["tree15", "tree64"])
+@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64), (W.TREE1, P.MDZ_TREE_1)],
+                         ids=["tree15", "tree64", "tree1"])
 def test_compiled_tables_equal_oracle_tree(spec, tid):
     t = P.medusa_tree_tables(tid)
     o = OT.build_tree(spec.caps, spec.budgets)

@@ -1,0 +1,56 @@
+"""CPU tests: the paper's metric definitions against the values it prints, and the oracle's single-node tree
+(one autoregressive step) against its causal decoder."""
+import numpy as np
+import pytest
+
+import workload as W
+from oracle import medusa as O
+from oracle import tree as OT
+from paper_2603_03383_amd import metrics as M
+from tests import util as U
+
+
+def test_speedup_and_overhead_reproduce_the_papers_printed_values():
+    # Section 4.3 prints AC 1.78, overhead 1.32 and speedup 1.35 at sequence length 128, and AC 1.65 with overhead 1.77
+    # (a slowdown) at length 1024
+    assert round(M.speedup(1.78, 1.32), 2) == 1.35
+    assert M.speedup(1.65, 1.77) < 1.0
+    assert M.overhead(2.64, 2.0) == pytest.approx(1.32)
+    assert M.break_even_ac(1.77) == 1.77
+    with pytest.raises(ValueError):
+        M.speedup(0.5, 1.2)
+    with pytest.raises(ValueError):
+        M.overhead(0.0, 1.0)
+
+
+def test_single_node_tree_tables():
+    t = OT.build_tree((), ())
+    assert t["T"] == 1 and t["K"] == 0 and t["n_cand"] == 1
+    assert t["parent"].tolist() == [-1] and t["depth"].tolist() == [0] and t["cand_slot"].tolist() == [0]
+    assert t["mask"].tolist() == [[True]] and t["retrieve"].tolist() == [[0]]
+
+
+def test_single_node_tree_step_is_one_causal_decode_step():
+    w = W.CONFIGS["cfg1_tiny_fp32"]
+    model = U.oracle_model(w, dtype="fp64")
+    tree1 = OT.build_tree((), ())
+    S = 9
+    toks = W.random_tokens(w, "ar_prefix", (S + 3,)).numpy()
+    kc, vc = O.empty_cache(model["cfg"], S + 4)
+    O.causal_decode(toks[:S], model, kc, vc, 0)
+    kc2, vc2 = U.copy_cache(kc), U.copy_cache(vc)
+    S_run = S
+    for tok in toks[S:]:                                   # three chained steps of the degenerate tree
+        ref_logits, ref_hidden = O.causal_decode([tok], model, kc, vc, S_run)
+        got = O.tree_verify_step(np.array([tok]), model, kc2, vc2, S_run, tree1)
+        np.testing.assert_allclose(got["logits"][0], ref_logits[0], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(got["hidden"][0], ref_hidden[0], rtol=0, atol=1e-12)
+        acc = O.accept_longest_prefix(tree1, np.array([tok]), got["node_argmax"])
+        assert acc["accept_len"] == 1 and acc["acc_nodes"].tolist() == [0] and acc["acc_tokens"].tolist() == [int(tok)]
+        assert acc["next_root"] == int(got["node_argmax"][0])
+        src, S_next = O.kv_compact(kc2, vc2, S_run, acc["acc_nodes"], acc["accept_len"])
+        assert src.tolist() == [S_run] and S_next == S_run + 1
+        S_run = S_next
+    for l in range(w.n_layers):
+        np.testing.assert_allclose(kc2[l][:, :S_run], kc[l][:, :S_run], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(vc2[l][:, :S_run], vc[l][:, :S_run], rtol=0, atol=1e-12)

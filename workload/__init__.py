@@ -142,6 +142,7 @@ class TreeSpec:
 
 TREE15 = TreeSpec("tree15", (2, 2, 2), (2, 4, 8), 15, 8)
 TREE64 = TreeSpec("tree64", (10, 10, 4, 4), (10, 12, 4, 3), 64, 38)
+TREE1 = TreeSpec("tree1", (), (), 1, 1)   # the root alone: one autoregressive decode step
 
 
 @dataclass(frozen=True)
