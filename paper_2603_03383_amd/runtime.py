@@ -106,6 +106,21 @@ class DeviceModel:
             C.cast(self._lm, C.POINTER(C.c_void_p)))
         return self
 
+    def view_with_tree(self, tree: str) -> "DeviceModel":
+        """A second model over the SAME packed weights with another static tree (e.g. "tree1": the autoregressive
+        baseline).  Medusa heads are kept only if the tree's depth matches their number."""
+        import copy
+        other = copy.copy(self)
+        d = self.desc
+        other.desc = B.ModelDesc(d.d, d.n_heads, d.head_dim, d.ffn, d.vocab, d.n_layers, d.dtype, B.TREES[tree],
+                                 d.rms_eps, d.rope_base)
+        other.tree = B.TREES[tree]
+        other.tree_info = B.medusa_tree_info(other.tree)
+        keep = len(self._heads) if other.tree_info["K"] == len(self._heads) else 0
+        w = self.weights
+        other.weights = B.Weights(w.layers, w.embed, w.lm_head, w.g_final, keep, w.head_w1, w.head_b1, w.head_lm)
+        return other
+
     def layer(self, l: int) -> B.LayerWeights:
         return self._layers[l]
 
