@@ -77,9 +77,11 @@ def build_device(w, with_heads):
     return dm, kv, max_prefix
 
 
-def cpu_baseline(w, with_heads, budget_layers=2):
-    """Times the oracle (as it stands) on a bounded sample: `budget_layers` decoder layers + final norm /
-    LM head / argmax (+ one Medusa head), then scales linearly to the full step."""
+def cpu_baseline(w, with_heads, budget_s=20.0):
+    """Times the oracle (as it stands) on sequence 0 of the workload: decoder layers one after the other until
+    `budget_s` seconds of oracle time are spent (all of them if they fit), then the final norm / LM head / argmax /
+    acceptance and the Medusa heads; layers not run are accounted for by linear scaling, and so are further
+    sequences of a batch.  Weights are generated layer by layer outside the timed regions."""
     import numpy as np
     import workload as W
     from oracle import medusa as O
@@ -96,21 +98,21 @@ def cpu_baseline(w, with_heads, budget_layers=2):
                rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype)
     gen = "cuda:0"
     S = w.prefix[0]
-    nl = min(budget_layers, w.n_layers)
     x = f32(W.hidden_state(w, "bench_x", T, gen)).astype(np.float64)
-    layers, caches = [], []
-    for l in range(nl):
+    t_layers, nl = 0.0, 0
+    for l in range(w.n_layers):
         lw = {m: f32(W.layer_weight(w, l, m, gen)) for m in W.LAYER_MATS}
         lw["g_attn"] = lw["g_ffn"] = np.ones(w.d, np.float32)
         k, v = W.prefix_kv(w, l, 0, gen)
         kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
         kc[:, :S] = f32(k); vc[:, :S] = f32(v)
-        layers.append(lw); caches.append((kc, vc))
-    t0 = time.perf_counter()
-    for lw, (kc, vc) in zip(layers, caches):
+        t0 = time.perf_counter()
         x = O.tree_verify_layer(x, lw, kc, vc, S, tree, cfg)
-    t_layers = time.perf_counter() - t0
-    del layers, caches
+        t_layers += time.perf_counter() - t0
+        nl += 1
+        del lw, kc, vc
+        if t_layers > budget_s:
+            break
     model = dict(cfg=cfg, g_final=np.ones(w.d, np.float32), lm_head=f32(W.lm_head(w, gen)))
     t0 = time.perf_counter()
     hidden, logits = O._final(x, model)
@@ -118,20 +120,24 @@ def cpu_baseline(w, with_heads, budget_layers=2):
     tokens = np.arange(T) % w.vocab
     O.accept_longest_prefix(tree, tokens, am)
     t_final = time.perf_counter() - t0
-    t_head = 0.0
+    t_heads, nh = 0.0, 0
     if with_heads:
-        head = dict(w1=f32(W.medusa_w1(w, 1, gen)), b1=None, lm=f32(W.medusa_lm(w, 1, gen)))
-        m1 = dict(model, medusa=[head])
-        tr1 = dict(tree, caps=tree["caps"][:1], cand_slot=np.zeros(T, np.int32))
-        t0 = time.perf_counter()
-        O.medusa_heads(hidden[0], m1, tr1)
-        t_head = (time.perf_counter() - t0) / 2.0          # the call also evaluates the base head: ~half is the head
-    per_seq = t_layers / nl * w.n_layers + t_final + t_head * w.n_medusa
+        for kh in range(1, w.n_medusa + 1):
+            head = dict(w1=f32(W.medusa_w1(w, kh, gen)), b1=None, lm=f32(W.medusa_lm(w, kh, gen)))
+            m1 = dict(model, medusa=[head])
+            tr1 = dict(tree, caps=tree["caps"][:1], cand_slot=np.zeros(T, np.int32))
+            t0 = time.perf_counter()
+            O.medusa_heads(hidden[0], m1, tr1)
+            t_heads += (time.perf_counter() - t0) / 2.0     # the call also evaluates the base head: ~half is the head
+            nh += 1
+            del head, m1
+    per_seq = t_layers / nl * w.n_layers + t_final + (t_heads / nh * w.n_medusa if nh else 0.0)
     est = per_seq * w.batch
     return dict(value=1.0 / est, unit="steps/s", cores=int(cores), kind="oracle",
                 sample=f"sequence 0: {nl} of {w.n_layers} layers ({t_layers:.2f} s) + final norm/LM head/argmax/accept "
-                       f"({t_final:.2f} s)" + (f" + 1 of {w.n_medusa} Medusa heads ({t_head:.2f} s)" if with_heads else "")
-                       + f", scaled linearly to the full step of {w.batch} sequence(s): {est:.1f} s/step")
+                       f"({t_final:.2f} s)" + (f" + {nh} of {w.n_medusa} Medusa heads ({t_heads:.2f} s)" if with_heads else "")
+                       + f"; {t_layers + t_final + t_heads:.1f} s of oracle time, scaled linearly to the full step of "
+                       f"{w.batch} sequence(s): {est:.1f} s/step")
 
 
 def main():
