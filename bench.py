@@ -232,6 +232,34 @@ def main():
         del buf_ar
         seq_len.copy_(seq0)
 
+    # the chained on-device loop (Section 3.2's device-resident, static-shape decode): N steps back to back, each
+    # step's root / hidden / lengths taken from the previous one on the device; eager launches vs one HIP graph replayed
+    chain = None
+    if not layer_only and with_heads:
+        n_chain = 16
+        cap_chain = max(w.prefix) + n_chain * (w.n_medusa + 1)
+        kv_c = P.DeviceKV(dm, batch=Bn, cap=cap_chain + T)
+        for b in range(Bn):
+            for l in range(w.n_layers):
+                k, v = W.prefix_kv(w, l, b, dm.device)
+                kv_c.write(l, b, 0, k, v)
+        chain = {"steps": n_chain}
+        for mode, use_graph in (("eager", False), ("graph", True)):
+            dec = P.ChainedDecoder(dm, kv_c, Bn, cap_chain, use_graph=use_graph)
+            for rep in range(2):                                       # first pass warms up / captures
+                dec.prime(hidden.view(Bn, w.d), root, seq0)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                toks, lens = dec.run(n_chain)
+                torch.cuda.synchronize()
+                dt_c = time.perf_counter() - t0
+            chain[f"ms_per_step_{mode}"] = dt_c / n_chain * 1e3
+            chain[f"tokens_per_s_{mode}"] = float(lens.sum().item()) / dt_c
+            del dec
+        chain["note"] = ("random-init heads accept only the root, so tokens/s here is steps/s x batch; multiply by a "
+                         "trained model's AC (the paper: 1.65-1.78) for its token rate")
+        del kv_c
+
     # practical read ceiling of this machine, measured now: the library's pure-read stream at 1 GB and at the dominant
     # kernel's average size
     from paper_2603_03383_amd.stream_calib import read_ceiling
@@ -275,6 +303,7 @@ def main():
         "kernel_us_per_step": {k: v["total_us"] / args.steps for k, v in prof.items()},
         "kernel_launches_per_step": {k: v["launches"] / args.steps for k, v in prof.items()},
         "paper_metrics": ar,
+        "chained_loop": chain,
         "paper_context": "paper reports only ratios: 1.35x end-to-end on an NPU, fp16, L=128 (not comparable)",
     }
     if not args.skip_cpu_baseline:

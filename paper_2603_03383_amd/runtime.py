@@ -196,3 +196,68 @@ def run_step(model: DeviceModel, kv: DeviceKV, buf: StepBuffers, hidden, src_row
                             buf.acc_nodes, buf.acc_tokens, buf.next_root, buf.last_node, stream)
     B.kv_compact(kv.desc, model.tree, buf.acc_nodes, buf.accept_len, seq_len, buf.kv_src_slots, Bn, buf.max_prefix,
                  stream)
+
+
+class ChainedDecoder:
+    """Speculative steps enqueued back to back with no host round trip (the paper's static-shape, device-resident
+    decode loop, Section 3.2): step i's heads read step i-1's hidden state at `last_node`, its root is step i-1's
+    `next_root`, and the sequence lengths live on the device.  With ``use_graph`` one step is captured in a HIP graph
+    and replayed.  Only argument marshalling and buffer bookkeeping happen here; every step of the method runs in the
+    library's kernels."""
+
+    def __init__(self, model: DeviceModel, kv: DeviceKV, batch: int, max_prefix: int, use_graph: bool = True):
+        self.model, self.kv, self.batch = model, kv, batch
+        self.buf = StepBuffers(model, batch, max_prefix)
+        self.seq_len = torch.zeros(batch, dtype=torch.int32, device=model.device)
+        self.use_graph = use_graph
+        self._graph = None
+
+    def prime(self, hidden0: torch.Tensor, root0: torch.Tensor, seq_len: torch.Tensor) -> None:
+        """hidden0 [B, d]: the hidden state the base model produced for the last prefix token; root0 [B]: its
+        greedy next token; seq_len [B]: prefix lengths."""
+        b = self.buf
+        b.hidden.zero_()
+        b.hidden[:, 0, :].copy_(hidden0)
+        b.last_node.zero_()
+        b.next_root.copy_(root0)
+        self.seq_len.copy_(seq_len)
+
+    def _step(self) -> None:
+        b = self.buf
+        run_step(self.model, self.kv, b, b.hidden, b.last_node, b.next_root, self.seq_len)
+
+    def _capture(self) -> None:
+        b = self.buf
+        saved = [t.clone() for t in (b.hidden, b.last_node, b.next_root, self.seq_len)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self._step()                                   # warm-up outside the capture (one-time kernel attributes)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for t, s in zip((b.hidden, b.last_node, b.next_root, self.seq_len), saved):
+            t.copy_(s)
+        torch.cuda.synchronize()
+        self._graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self._graph, stream=side):
+            self._step()
+        for t, s in zip((b.hidden, b.last_node, b.next_root, self.seq_len), saved):
+            t.copy_(s)                                     # capture does not run the kernels; restore anyway
+
+    def run(self, n_steps: int):
+        """Enqueues n_steps steps; returns device tensors (tokens [n_steps, B, K+1] with -1 padding,
+        accept_len [n_steps, B]).  The caller synchronises when it wants to read them."""
+        b = self.buf
+        K1 = b.acc_tokens.shape[1]
+        tokens = torch.empty(n_steps, self.batch, K1, dtype=torch.int32, device=self.model.device)
+        lens = torch.empty(n_steps, self.batch, dtype=torch.int32, device=self.model.device)
+        if self.use_graph and self._graph is None:
+            self._capture()
+        for i in range(n_steps):
+            if self._graph is not None:
+                self._graph.replay()
+            else:
+                self._step()
+            tokens[i].copy_(b.acc_tokens)
+            lens[i].copy_(b.accept_len)
+        return tokens, lens
