@@ -306,6 +306,19 @@ def main():
         "chained_loop": chain,
         "paper_context": "paper reports only ratios: 1.35x end-to-end on an NPU, fp16, L=128 (not comparable)",
     }
+    if "gemm_large" in prof and prof["gemm_large"]["launches"]:
+        # several sequences at once: the layer GEMMs run at M = batch * T rows and are bound by the matrix cores
+        gl = prof["gemm_large"]
+        elems = w.n_layers * (4 * w.d * w.d + 3 * w.d * w.ffn) + (0 if layer_only else w.vocab * w.d)
+        flops = 2.0 * Bn * T * elems
+        tf = flops / (gl["total_us"] / args.steps * 1e-6) / 1e12
+        out["roofline"] = {"kernel": "gemm_large_kernel (every GEMM of the step at M = %d rows)" % (Bn * T), "bound": "mfma",
+                           "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
+                           "algorithmic_flops_per_launch": flops / (gl["launches"] / args.steps),
+                           "launches_per_step": gl["launches"] / args.steps,
+                           "avg_launch_us": gl["total_us"] / gl["launches"],
+                           "measured": "HIP events on the launch stream around every launch, %d instrumented steps "
+                                       "after the timed region" % args.steps}
     if not args.skip_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, with_heads)
     print(json.dumps(out))

@@ -27,9 +27,17 @@ int gemm_mfma_slots(int M, int N, int K, int max_split);
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
                      int max_split, Partials* res, hipStream_t st);
 
+bool gemm_large_supported(int dtype, int M, int N, int K);
+int gemm_large_slots(int M, int N, int K);
+int launch_gemm_large(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
+                      Partials* res, hipStream_t st);
+
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld, int max_split,
                 Partials* res, hipStream_t st) {
   *res = single_slot(out, (int64_t)M * ld, ld);
+  // several sequences at once: the MFMA-bound kernel (it splits K only when the caller's consumer reduces slots)
+  if (gemm_large_supported(dtype, M, N, K) && (max_split > 1 || gemm_large_slots(M, N, K) == 1))
+    return launch_gemm_large(X, Wp, out, M, N, K, ld, res->stride, res, st);
   const int rows_per_launch = M <= 64 ? M : 64;
   if (gemm_mfma_supported(dtype, rows_per_launch, N, K) && (M <= 64 || M % 64 == 0)) {
     // More than 64 rows (several sequences): one launch per block of 64 rows.  Every launch uses the same plan, so
@@ -49,6 +57,7 @@ int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int
 static int max_split_for(int rows) { return (rows <= 64 || rows % 64 == 0) ? 12 : 1; }
 // fp32 elements of partial-sum workspace a [rows, N] = [rows, K] x [N, K] GEMM needs
 static int64_t gemm_part_elems(int dtype, int rows, int N, int K) {
+  if (gemm_large_supported(dtype, rows, N, K)) return (int64_t)gemm_large_slots(rows, N, K) * rows * N;
   const int per = rows <= 64 ? rows : 64;
   const int slots = (gemm_mfma_supported(dtype, per, N, K) && (rows <= 64 || rows % 64 == 0))
                         ? gemm_mfma_slots(per, N, K, max_split_for(rows))

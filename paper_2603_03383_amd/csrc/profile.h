@@ -8,10 +8,11 @@ namespace mdz {
 
 enum ProfTag {
   PROF_GEMM = 0,     // portable GEMM
-  PROF_GEMM_W64,     // gemm_mfma_kernel<4,1,2,*>: 128-column bands, 64 rows (QKV, gate/up, LM head)
-  PROF_GEMM_N64,     // gemm_mfma_kernel<2,1,2,*>: 64-column bands, 64 rows (O, down)
-  PROF_GEMM_W32,     // gemm_mfma_kernel<4,*,1,*>: <= 32 rows (Medusa head LM matrices)
-  PROF_GEMM_N32,     // gemm_mfma_kernel<2,1,1,*>: <= 32 rows (Medusa head W1)
+  PROF_GEMM_W64,     // gemm_mfma_kernel<4,1,2,*>: 128-column bands, 64 rows (every layer GEMM and the LM head)
+  PROF_GEMM_N64,     // gemm_mfma_kernel<2,1,2,*>: 64-column bands, 64 rows (development plans only)
+  PROF_GEMM_W32,     // gemm_mfma_kernel<4,1,1,*>: <= 32 rows (Medusa heads, autoregressive step)
+  PROF_GEMM_N32,     // gemm_mfma_kernel<2,1,1,*>: <= 32 rows (development plans only)
+  PROF_GEMM_LARGE,   // gemm_large_kernel: >= 128 rows (several sequences)
   PROF_ATTN,         // tree-masked attention (+ its combine pass)
   PROF_NORM,         // RMSNorm
   PROF_ROPE,         // RoPE table, RoPE + KV write

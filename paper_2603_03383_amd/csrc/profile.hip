@@ -18,7 +18,7 @@ struct State {
   int cap = 0;
   int dropped = 0;
 } g;
-const char* kNames[PROF_NUM_TAGS] = {"gemm_portable", "gemm_w64", "gemm_n64", "gemm_w32", "gemm_n32", "attention", "rmsnorm", "rope", "swiglu",
+const char* kNames[PROF_NUM_TAGS] = {"gemm_portable", "gemm_w64", "gemm_n64", "gemm_w32", "gemm_n32", "gemm_large", "attention", "rmsnorm", "rope", "swiglu",
                                      "embed", "select", "accept", "kv_compact", "misc"};
 }  // namespace
 
