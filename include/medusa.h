@@ -144,6 +144,16 @@ int medusa_stream_copy(const void* src, void* dst, int64_t bytes, void* stream);
 /* Rows per packed tile for a dtype (32 for bf16, 16 for fp32). */
 int medusa_pack_tile_rows(int dtype);
 
+/* Host-only introspection of the weight-streaming GEMM's work decomposition for X[M,K] x W[N,K]^T (bf16, M <= 64,
+ * N % 32 == 0, K % 128 == 0), so that tests can audit it; nothing is enqueued.  The (column band, K-stage) units,
+ * numbered band-major, are cut into `grid` equal contiguous ranges, range w = [floor(w*U/grid), floor((w+1)*U/grid)),
+ * U = (N / band_cols rounded up) * n_stages; every range that touches a band writes one partial-sum slot of it.
+ * max_split bounds the slots per band (1: whole bands only).  medusa_gemm_slot_count returns the number of slots the
+ * consumers add for output column `col` (negative: error). */
+int medusa_gemm_plan(int dtype, int M, int N, int K, int max_split, int32_t* grid, int32_t* band_cols, int32_t* n_stages,
+                     int32_t* max_slots);
+int medusa_gemm_slot_count(int dtype, int M, int N, int K, int max_split, int col);
+
 /* Bytes of a packed [n_rows, k] matrix (bf16: n_rows rounded up to 128 and k to 256; fp32: n_rows to 16). */
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
 

@@ -57,6 +57,8 @@ _lib = None
 _SIGNATURES = {
     "medusa_tree_info": (C.c_int, [C.c_int] + [C.c_void_p] * 5),
     "medusa_tree_tables": (C.c_int, [C.c_int] + [C.c_void_p] * 5),
+    "medusa_gemm_plan": (C.c_int, [C.c_int] * 5 + [C.c_void_p] * 4),
+    "medusa_gemm_slot_count": (C.c_int, [C.c_int] * 6),
     "medusa_last_error": (C.c_char_p, []),
     "medusa_profile_begin": (C.c_int, [C.c_int]),
     "medusa_profile_end": (C.c_int, [C.c_char_p, C.c_int64]),
@@ -131,6 +133,18 @@ def medusa_tree_info(tree: int) -> dict:
     topk = (C.c_int32 * MDZ_MAX_HEADS)()
     _check(lib().medusa_tree_info(tree, C.byref(T), C.byref(K), C.byref(P), C.byref(NC), topk))
     return dict(T=T.value, K=K.value, n_paths=P.value, n_cand=NC.value, topk=tuple(topk[:K.value]))
+
+
+def medusa_gemm_plan(dtype: int, M: int, N: int, K: int, max_split: int) -> dict:
+    vals = [C.c_int32() for _ in range(4)]
+    _check(lib().medusa_gemm_plan(dtype, M, N, K, max_split, *[C.byref(v) for v in vals]))
+    return dict(zip(("grid", "band_cols", "n_stages", "max_slots"), [v.value for v in vals]))
+
+
+def medusa_gemm_slot_count(dtype: int, M: int, N: int, K: int, max_split: int, col: int) -> int:
+    n = lib().medusa_gemm_slot_count(dtype, M, N, K, max_split, col)
+    _check(n)
+    return n
 
 
 def medusa_tree_tables(tree: int) -> dict:

@@ -276,6 +276,20 @@ bool gemm_mfma_supported(int dtype, int M, int N, int K) {
   return dtype == MDZ_BF16 && M >= 1 && M <= 64 && N % 32 == 0 && K % 128 == 0 && K >= 128;
 }
 
+// The decomposition launch_gemm_mfma will use, as the consumers see it (no GPU work): fills the slot-count fields of
+// *res and, if grid is given, the number of workgroups.
+void gemm_mfma_describe(int M, int N, int K, int max_split, Partials* res, int* grid) {
+  const GemmPlan p = plan_gemm(M, N, K, max_split);
+  const int n_tiles = N / 32, n_stages = K / p.ck;
+  const int bands = (n_tiles + p.wpb * p.nt - 1) / (p.wpb * p.nt);
+  res->band_cols = p.wpb * p.nt * 32;
+  res->n_stages = n_stages;
+  res->split_units = (uint32_t)bands * n_stages;
+  res->split_grid = p.whole ? 0 : (uint32_t)p.grid;
+  res->n = p.slots;
+  if (grid) *grid = p.grid;
+}
+
 // Writes partial sums into slots of P (slot s at P + s*part_stride, each [M][ldp] fp32) and fills the fields of
 // *res that describe how many slots each band of columns received (one everywhere when max_split <= 1).
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
@@ -289,11 +303,7 @@ int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int 
   const int bands = (n_tiles + p.wpb * p.nt - 1) / (p.wpb * p.nt);
   MDZ_REQUIRE((int64_t)bands * n_stages * p.grid < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: %d x %d units on %d workgroups overflow",
               bands, n_stages, p.grid);
-  res->band_cols = p.wpb * p.nt * 32;
-  res->n_stages = n_stages;
-  res->split_units = (uint32_t)bands * n_stages;
-  res->split_grid = p.whole ? 0 : (uint32_t)p.grid;
-  res->n = p.slots;
+  gemm_mfma_describe(M, N, K, max_split, res, nullptr);
   const bf16_t* x = (const bf16_t*)X;
   const bf16_t* w = (const bf16_t*)Wp;
 #define MDZ_GEMM_CASE(WPB, NT, MT, CK)                                                                       \

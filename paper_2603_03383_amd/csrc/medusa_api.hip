@@ -24,6 +24,7 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K);
 int gemm_mfma_slots(int M, int N, int K, int max_split);
+void gemm_mfma_describe(int M, int N, int K, int max_split, Partials* res, int* grid);
 int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
                      int max_split, Partials* res, hipStream_t st);
 
@@ -270,6 +271,27 @@ int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_
 int medusa_pack_tile_rows(int dtype) {
   MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
   return dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
+}
+
+int medusa_gemm_plan(int dtype, int M, int N, int K, int max_split, int32_t* grid, int32_t* band_cols, int32_t* n_stages,
+                     int32_t* max_slots) {
+  MDZ_REQUIRE(gemm_mfma_supported(dtype, M, N, K), MDZ_EUNSUPPORTED, "gemm plan: [%d,%d] x [%d,%d] is not a streaming-GEMM shape",
+              M, K, N, K);
+  Partials pr = single_slot(nullptr, 0, 0);
+  int g = 0;
+  gemm_mfma_describe(M, N, K, max_split, &pr, &g);
+  if (grid) *grid = g;
+  if (band_cols) *band_cols = pr.band_cols;
+  if (n_stages) *n_stages = pr.n_stages;
+  if (max_slots) *max_slots = pr.n;
+  return MDZ_OK;
+}
+
+int medusa_gemm_slot_count(int dtype, int M, int N, int K, int max_split, int col) {
+  MDZ_REQUIRE(gemm_mfma_supported(dtype, M, N, K) && col >= 0 && col < N, MDZ_EINVAL, "gemm slot count: bad arguments");
+  Partials pr = single_slot(nullptr, 0, 0);
+  gemm_mfma_describe(M, N, K, max_split, &pr, nullptr);
+  return pr.count(col);
 }
 
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k) {
