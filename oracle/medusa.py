@@ -88,33 +88,40 @@ def rope(x, pos, base):
 
 
 def _attend(q, kc, vc, visible, head_dim):
-    """q [H,n,hd]; kc,vc [H,cap,hd]; visible [n, n_slots] bool over cache slots 0..n_slots-1."""
+    """q [H,n,hd]; kc,vc [Hkv,cap,hd]; visible [n, n_slots] bool over cache slots 0..n_slots-1.
+    Grouped-query attention: query head h reads key/value head h // (H // Hkv) (Hkv == H: plain multi-head)."""
     n_slots = visible.shape[1]
     out = np.empty_like(q)
     scale = 1.0 / np.sqrt(float(head_dim))
+    group = q.shape[0] // kc.shape[0]
     for h in range(q.shape[0]):
-        sc = (q[h] @ kc[h, :n_slots].T) * scale
+        hk = h // group
+        sc = (q[h] @ kc[hk, :n_slots].T) * scale
         sc = np.where(visible, sc, -np.inf)
         sc = sc - sc.max(axis=1, keepdims=True)
         p = np.exp(sc)
         p = p / p.sum(axis=1, keepdims=True)
-        out[h] = p @ vc[h, :n_slots]
+        out[h] = p @ vc[hk, :n_slots]
     return out
 
 
 def _layer(x, lw, kc, vc, slots, pos, visible, cfg):
     """One pre-norm decoder layer over n rows.
-    x [n,d]; kc,vc [H,cap,hd] (this layer's cache, written in place at ``slots``);
-    pos [n] RoPE positions; visible [n, n_slots] which cache slots each row attends."""
+    x [n,d]; kc,vc [Hkv,cap,hd] (this layer's cache, written in place at ``slots``);
+    pos [n] RoPE positions; visible [n, n_slots] which cache slots each row attends.
+    cfg["n_kv_heads"] (default n_heads) key/value heads: wk, wv are [Hkv*hd, d] (Table 1 of the paper: 32 query
+    heads, 8 key/value heads)."""
     H, hd = cfg["n_heads"], cfg["head_dim"]
+    Hkv = cfg.get("n_kv_heads") or H
+    assert H % Hkv == 0
     n = x.shape[0]
     xn = rmsnorm(x, lw["g_attn"], cfg["rms_eps"])
     q = xn @ np.asarray(lw["wq"], dtype=F64).T
     k = xn @ np.asarray(lw["wk"], dtype=F64).T
     v = xn @ np.asarray(lw["wv"], dtype=F64).T
     q = rope(q.reshape(n, H, hd).transpose(1, 0, 2), pos, cfg["rope_base"])      # [H,n,hd]
-    k = rope(k.reshape(n, H, hd).transpose(1, 0, 2), pos, cfg["rope_base"])
-    v = v.reshape(n, H, hd).transpose(1, 0, 2)
+    k = rope(k.reshape(n, Hkv, hd).transpose(1, 0, 2), pos, cfg["rope_base"])        # [Hkv,n,hd]
+    v = v.reshape(n, Hkv, hd).transpose(1, 0, 2)
     kc[:, slots, :] = round_to_storage(k, cfg["dtype"])
     vc[:, slots, :] = round_to_storage(v, cfg["dtype"])
     att = _attend(q, kc, vc, visible, hd)                                          # [H,n,hd]
@@ -185,7 +192,7 @@ def causal_decode(tokens, model, kcache, vcache, S):
 
 
 def empty_cache(cfg, cap):
-    shape = (cfg["n_heads"], cap, cfg["head_dim"])
+    shape = (cfg.get("n_kv_heads") or cfg["n_heads"], cap, cfg["head_dim"])
     return ([np.zeros(shape, dtype=F64) for _ in range(cfg["n_layers"])],
             [np.zeros(shape, dtype=F64) for _ in range(cfg["n_layers"])])
 

@@ -15,7 +15,7 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 
 
 def oracle_cfg(w: W.Workload, dtype=None) -> dict:
-    return dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn,
+    return dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, n_kv_heads=w.kv_heads, head_dim=w.head_dim, ffn=w.ffn,
                 vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=dtype or w.dtype)
 
 

@@ -161,6 +161,11 @@ class Workload:
     rms_eps: float = 1e-5
     weight_std: float = 0.02
     seed: int = BASE_SEED
+    n_kv_heads: int = 0        # key/value heads (grouped-query attention); 0 = n_heads (plain multi-head attention)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
 
     @property
     def batch(self) -> int:
@@ -216,7 +221,8 @@ LAYER_MATS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
 
 
 def layer_shapes(w: Workload) -> Dict[str, Tuple[int, int]]:
-    return {"wq": (w.d, w.d), "wk": (w.d, w.d), "wv": (w.d, w.d), "wo": (w.d, w.d),
+    kvd = w.kv_heads * w.head_dim
+    return {"wq": (w.d, w.d), "wk": (kvd, w.d), "wv": (kvd, w.d), "wo": (w.d, w.d),
             "wgate": (w.ffn, w.d), "wup": (w.ffn, w.d), "wdown": (w.d, w.ffn)}
 
 
@@ -247,9 +253,9 @@ def medusa_lm(w: Workload, k: int, device="cpu") -> torch.Tensor:
 
 
 def prefix_kv(w: Workload, layer: int, seq: int, device="cpu"):
-    """Random prefix K and V, each [n_heads, S, head_dim], N(0,1)-like, storage dtype."""
+    """Random prefix K and V, each [kv_heads, S, head_dim], N(0,1)-like, storage dtype."""
     S = w.prefix[seq]
-    shape = (w.n_heads, S, w.head_dim)
+    shape = (w.kv_heads, S, w.head_dim)
     k = normal(w.seed, f"kv.k.l{layer}.s{seq}", shape, 1.0, w.torch_dtype, device)
     v = normal(w.seed, f"kv.v.l{layer}.s{seq}", shape, 1.0, w.torch_dtype, device)
     return k, v
