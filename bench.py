@@ -34,11 +34,12 @@ def algorithmic_bytes(w, with_heads: bool):
     written and read once, the embedding rows gathered.  Activations (<= 1.4 MB each) are not counted."""
     es = 2 if w.dtype == "bf16" else 4
     T, K = w.tree.n_nodes, w.n_medusa
-    layer_w = (4 * w.d * w.d + 3 * w.d * w.ffn) * es
+    kvd = w.kv_heads * w.head_dim
+    layer_w = (2 * w.d * w.d + 2 * kvd * w.d + 3 * w.d * w.ffn) * es
     gemm_layers = w.n_layers * layer_w
     lm = w.vocab * w.d * es
     heads = K * (w.d * w.d + w.vocab * w.d) * es if with_heads else 0
-    kv_row = 2 * w.n_heads * w.head_dim * es                      # K and V of one slot, one layer
+    kv_row = 2 * kvd * es                                         # K and V of one slot, one layer
     kv_prefix = sum(w.prefix) * kv_row * w.n_layers
     kv_tree = 2 * w.batch * T * kv_row * w.n_layers               # written + read
     embed = w.batch * T * w.d * es
@@ -55,7 +56,7 @@ def build_device(w, with_heads):
     import paper_2603_03383_amd as P
     dev = "cuda:0"
     dm = P.DeviceModel(d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn, vocab=w.vocab, n_layers=w.n_layers,
-                       dtype=w.dtype, tree=w.tree.name, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev)
+                       dtype=w.dtype, tree=w.tree.name, n_kv_heads=w.n_kv_heads, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev)
     for l in range(w.n_layers):
         mats = [W.layer_weight(w, l, m, dev) for m in W.LAYER_MATS]
         dm.add_layer(*mats, W.norm_gain(w, "g", dev), W.norm_gain(w, "g", dev))
@@ -94,8 +95,8 @@ def cpu_baseline(w, with_heads, budget_s=20.0):
     f32 = lambda t: t.detach().to("cpu").float().numpy()
     tree = OT.build_tree(w.tree.caps, w.tree.budgets)
     T = tree["T"]
-    cfg = dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn, vocab=w.vocab,
-               rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype)
+    cfg = dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, n_kv_heads=w.kv_heads, head_dim=w.head_dim, ffn=w.ffn,
+               vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype)
     gen = "cuda:0"
     S = w.prefix[0]
     x = f32(W.hidden_state(w, "bench_x", T, gen)).astype(np.float64)
@@ -104,7 +105,7 @@ def cpu_baseline(w, with_heads, budget_s=20.0):
         lw = {m: f32(W.layer_weight(w, l, m, gen)) for m in W.LAYER_MATS}
         lw["g_attn"] = lw["g_ffn"] = np.ones(w.d, np.float32)
         k, v = W.prefix_kv(w, l, 0, gen)
-        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc = np.zeros((w.kv_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
         kc[:, :S] = f32(k); vc[:, :S] = f32(v)
         t0 = time.perf_counter()
         x = O.tree_verify_layer(x, lw, kc, vc, S, tree, cfg)
@@ -309,7 +310,7 @@ def main():
     if "gemm_large" in prof and prof["gemm_large"]["launches"]:
         # several sequences at once: the layer GEMMs run at M = batch * T rows and are bound by the matrix cores
         gl = prof["gemm_large"]
-        elems = w.n_layers * (4 * w.d * w.d + 3 * w.d * w.ffn) + (0 if layer_only else w.vocab * w.d)
+        elems = w.n_layers * (2 * w.d * w.d + 2 * w.kv_heads * w.head_dim * w.d + 3 * w.d * w.ffn) + (0 if layer_only else w.vocab * w.d)
         flops = 2.0 * Bn * T * elems
         tf = flops / (gl["total_us"] / args.steps * 1e-6) / 1e12
         out["roofline"] = {"kernel": "gemm_large_kernel (every GEMM of the step at M = %d rows)" % (Bn * T), "bound": "mfma",

@@ -51,17 +51,21 @@ typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1 } mdz_dtype;
 
 #define MDZ_MAX_HEADS 8
 
-/* HOST struct: the decoder's shape. d == n_heads * head_dim (multi-head attention, no bias). */
+/* HOST struct: the decoder's shape. d == n_heads * head_dim (no bias).  n_kv_heads: key/value heads of
+ * grouped-query attention (Table 1 of the paper: 32 query heads, 8 key/value heads); it must divide n_heads, query
+ * head h reads key/value head h / (n_heads / n_kv_heads); 0 means n_heads (plain multi-head attention). */
 typedef struct {
   int32_t d, n_heads, head_dim, ffn, vocab, n_layers;
   int32_t dtype; /* mdz_dtype */
   int32_t tree;  /* mdz_tree_id: fixes T, K and the per-head top-k sizes */
   float rms_eps;
   float rope_base;
+  int32_t n_kv_heads;
 } mdz_model_desc;
 
 /* HOST struct of device pointers: one decoder layer.  Matrices are in the library's PACKED layout
- * (see medusa_pack_weight): wqkv = rows of Wq, Wk, Wv stacked ([3d, d]); wgateup = Wgate and Wup with
+ * (see medusa_pack_weight): wqkv = rows of Wq, Wk, Wv stacked
+ * ([d + 2 * n_kv_heads * head_dim, d]: 3d for multi-head attention); wgateup = Wgate and Wup with
  * their row tiles interleaved (tile 2j = gate tile j, tile 2j+1 = up tile j; [2*ffn, d]).
  * g_attn, g_ffn: RMSNorm gains [d], storage dtype. */
 typedef struct {
@@ -95,7 +99,7 @@ typedef struct {
 typedef struct {
   void* k;
   void* v;
-  int32_t n_layers, batch, n_heads, head_dim, cap;
+  int32_t n_layers, batch, n_heads, head_dim, cap; /* n_heads: key/value heads (the heads the cache holds) */
   int32_t dtype; /* mdz_dtype */
 } mdz_kv_desc;
 
@@ -161,7 +165,7 @@ int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
  * features: y = W x) into the streaming order of the GEMM kernels, same element type, same bytes.
  * Source row tile j (rows j*R .. j*R+R-1, R = medusa_pack_tile_rows) lands at tile index
  * tile_offset + j*tile_stride of `dst`, a packed matrix of dst_rows rows in total, so several matrices
- * can be stacked (wqkv: offsets 0, d/R, 2d/R, stride 1) or interleaved (wgateup: offsets 0 and 1,
+ * can be stacked (wqkv: offsets 0, d/R, (d + kv width)/R, stride 1) or interleaved (wgateup: offsets 0 and 1,
  * stride 2).  n_rows must be a multiple of R unless tile_stride == 1 and this is the last matrix. */
 int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, void* stream);

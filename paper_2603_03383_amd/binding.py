@@ -33,7 +33,7 @@ class MedusaError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
                 ("vocab", C.c_int32), ("n_layers", C.c_int32), ("dtype", C.c_int32), ("tree", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int32)]
 
 
 class LayerWeights(C.Structure):

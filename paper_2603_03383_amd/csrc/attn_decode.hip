@@ -45,7 +45,7 @@ __global__ void __launch_bounds__(256)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int key = lane & 31, half = lane >> 5;
   const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y, b = blockIdx.z;
-  const int d = g.n_heads * kHD;
+  const int d = q_heads(g) * kHD;
   const int S = min(max(seq_len[b], 0), max_prefix);
   const int n_slots = S + 1;  // the prefix and the node itself
   const int nb = (n_slots + 31) >> 5;
@@ -62,7 +62,7 @@ __global__ void __launch_bounds__(256)
     for (int e = 0; e < 8; ++e) qf[ks][e] *= scale_log2;
   }
 
-  const int64_t head_base = kv_head_base(g, layer, b, h);
+  const int64_t head_base = kv_head_base(g, layer, b, h / g.group);  // query head h reads key/value head h / group
   const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
   const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
 
@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(256)
     if (n_splits == 1) {
       att_out[(int64_t)b * d + h * kHD + f] = float_to_bf16(acc / L);
     } else {
-      const int64_t pidx = (int64_t)(b * g.n_heads + h) * n_splits + split;
+      const int64_t pidx = (int64_t)(b * q_heads(g) + h) * n_splits + split;
       part_o[pidx * kHD + f] = acc;
       if (f == 0) part_ml[pidx * 2] = M, part_ml[pidx * 2 + 1] = L;
     }
@@ -177,16 +177,17 @@ int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, cons
                             int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
-  const int splits = decode_splits(B, g.n_heads, max_prefix);
-  MDZ_REQUIRE(scratch_bytes >= attn_decode_scratch_bytes(B, g.n_heads, max_prefix), MDZ_EWORKSPACE,
+  const int nq = q_heads(g);
+  const int splits = decode_splits(B, nq, max_prefix);
+  MDZ_REQUIRE(scratch_bytes >= attn_decode_scratch_bytes(B, nq, max_prefix), MDZ_EWORKSPACE,
               "decode attention: scratch too small");
   float* part_o = (float*)scratch;
-  float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kHD;
-  attn_decode_kernel<<<dim3(splits, g.n_heads, B), 256, 0, st>>>((const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
+  float* part_ml = part_o + (int64_t)B * nq * splits * kHD;
+  attn_decode_kernel<<<dim3(splits, nq, B), 256, 0, st>>>((const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
                                                                  layer, seq_len, max_prefix, (bf16_t*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_decode_combine_kernel<<<dim3(g.n_heads, B), 128, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
+    attn_decode_combine_kernel<<<dim3(nq, B), 128, 0, st>>>(nq, splits, part_o, part_ml, (bf16_t*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;

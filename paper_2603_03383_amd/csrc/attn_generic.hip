@@ -30,7 +30,8 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(int tree, const T* __
   __shared__ float red[4];
   const int row = blockIdx.x, h = blockIdx.y;
   const int b = row / t.T, i = row % t.T;
-  const int hd = g.head_dim, d = g.n_heads * hd;
+  const int hd = g.head_dim, d = q_heads(g) * hd;
+  const int hk = h / g.group;  // the key/value head this query head reads
   const int S = min(max(seq_len[b], 0), max_prefix);
   const int n_slots = S + t.T;
   const uint64_t mask = t.anc_mask[i];
@@ -47,7 +48,7 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(int tree, const T* __
       float s = -INFINITY;
       if (vis) {
         s = 0.f;
-        for (int e = 0; e < hd; ++e) s += qs[e] * to_float(kc[k_index(g, layer, b, h, j, e)]);
+        for (int e = 0; e < hd; ++e) s += qs[e] * to_float(kc[k_index(g, layer, b, hk, j, e)]);
       }
       p[j - c0] = s;
       lm = fmaxf(lm, s);
@@ -77,7 +78,7 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(int tree, const T* __
     l_run = l_run * old_scale + csum;
     if (tid < hd) {
       float a = acc * old_scale;
-      for (int j = c0; j < c1; ++j) a += p[j - c0] * to_float(vc[v_index(g, layer, b, h, j, tid)]);
+      for (int j = c0; j < c1; ++j) a += p[j - c0] * to_float(vc[v_index(g, layer, b, hk, j, tid)]);
       acc = a;
     }
     m_run = m_new;
@@ -93,7 +94,7 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
   const TreeTables* t = host_tree(tree);
   if (B == 0) return MDZ_OK;
   MDZ_REQUIRE(g.head_dim <= 256, MDZ_EUNSUPPORTED, "attention: head_dim %d > 256", g.head_dim);
-  dim3 grid(B * t->T, g.n_heads);
+  dim3 grid(B * t->T, q_heads(g));
   if (dtype == MDZ_BF16)
     attn_generic_kernel<bf16_t><<<grid, 256, 0, st>>>(tree, (const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
                                                       layer, seq_len, max_prefix, (bf16_t*)att_out);

@@ -46,19 +46,19 @@ __device__ inline u32x4 pack_bf16x8(const float* v) {
 // NM head-matrices (q, or q k v, of head h) of the QKV GEMM output for the prologue below: thread (row = t/4,
 // seg = t%4) sums the partial-sum slots (in order) of features [16*seg, 16*seg+16) and their rotary partners
 // [64 + 16*seg, ...) of each matrix: lo[m][16], hi[m][16].  The loads of one slot of all NM matrices are issued
-// together (8 float4 per matrix in flight per thread); matrix m starts at column col0 + m * col_step.
+// together (8 float4 per matrix in flight per thread); matrix m starts at column cols[m].
 template <int NM>
-__device__ inline void qkv_gather(const Partials& part, int64_t row, int col0, int col_step, int seg, float (&lo)[NM][16],
+__device__ inline void qkv_gather(const Partials& part, int64_t row, const int (&cols)[NM], int seg, float (&lo)[NM][16],
                                   float (&hi)[NM][16]) {
   int n_part[NM], n_max = 0;
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
-    n_part[m] = part.count(col0 + m * col_step);
+    n_part[m] = part.count(cols[m]);
     n_max = n_part[m] > n_max ? n_part[m] : n_max;
 #pragma unroll
     for (int i = 0; i < 16; ++i) lo[m][i] = hi[m][i] = 0.f;
   }
-  const float* src = part.p + row * part.ld + col0 + 16 * seg;
+  const float* src = part.p + row * part.ld + 16 * seg;
   for (int p = 0; p < n_max; ++p) {
     float4 a[NM][4], b[NM][4];
     const float* sp = src + (int64_t)p * part.stride;
@@ -67,8 +67,8 @@ __device__ inline void qkv_gather(const Partials& part, int64_t row, int col0, i
       if (p < n_part[m]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          a[m][i] = *reinterpret_cast<const float4*>(sp + m * col_step + 4 * i);
-          b[m][i] = *reinterpret_cast<const float4*>(sp + m * col_step + 64 + 4 * i);
+          a[m][i] = *reinterpret_cast<const float4*>(sp + cols[m] + 4 * i);
+          b[m][i] = *reinterpret_cast<const float4*>(sp + cols[m] + 64 + 4 * i);
         }
       }
 #pragma unroll
@@ -109,7 +109,8 @@ __global__ void __launch_bounds__(256)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qi = lane & 31, gh = lane >> 5;
   const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y, b = blockIdx.z;
-  const int d = g.n_heads * kHD;
+  const int hk = h / g.group;  // the key/value head that query head h reads (grouped-query attention)
+  const int d = q_heads(g) * kHD, dkv = g.n_heads * kHD;
   const int S = min(max(seq_len[b], 0), max_prefix);
   const int n_slots = S + kTQ;
   const int nb = (n_slots + 31) >> 5;
@@ -147,24 +148,27 @@ __global__ void __launch_bounds__(256)
       *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack_bf16x8(hi + 8);
     };
     if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
+      // (the query heads of one group all produce their shared key/value rows: identical values, no ordering needed)
       float lo[3][16], hi[3][16];
-      qkv_gather<3>(qkv, grow, h * kHD, d, seg, lo, hi);
+      const int cols[3] = {h * kHD, d + hk * kHD, d + dkv + hk * kHD};  // columns of q, k, v in the QKV output
+      qkv_gather<3>(qkv, grow, cols, seg, lo, hi);
       stage_q(lo[0], hi[0]);
       const int slot = S + row;
       rope16(cs_row, seg, lo[1], hi[1]);
       // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg)) = pack_bf16x8(lo[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 16 * seg + 8)) = pack_bf16x8(lo[1] + 8);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg)) = pack_bf16x8(hi[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, h, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi[1] + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack_bf16x8(lo[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack_bf16x8(lo[1] + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack_bf16x8(hi[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi[1] + 8);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        vc[v_index(g, layer, b, h, slot, 16 * seg + i)] = float_to_bf16(lo[2][i]);
-        vc[v_index(g, layer, b, h, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[2][i]);
+        vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = float_to_bf16(lo[2][i]);
+        vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[2][i]);
       }
     } else {
       float lo[1][16], hi[1][16];
-      qkv_gather<1>(qkv, grow, h * kHD, d, seg, lo, hi);
+      const int cols[1] = {h * kHD};
+      qkv_gather<1>(qkv, grow, cols, seg, lo, hi);
       stage_q(lo[0], hi[0]);
     }
   }
@@ -174,7 +178,7 @@ __global__ void __launch_bounds__(256)
   const uint64_t mq[2] = {t.anc_mask[qi], t.anc_mask[32 + qi]};
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
 
-  const int64_t head_base = kv_head_base(g, layer, b, h);
+  const int64_t head_base = kv_head_base(g, layer, b, hk);
   const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
   const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
 
@@ -346,7 +350,7 @@ __global__ void __launch_bounds__(256)
           uint2{(uint32_t)v0.bits | ((uint32_t)v1.bits << 16), (uint32_t)v2.bits | ((uint32_t)v3.bits << 16)};
     }
   } else {
-    const int64_t pidx = ((int64_t)(b * g.n_heads + h) * n_splits + split);
+    const int64_t pidx = ((int64_t)(b * q_heads(g) + h) * n_splits + split);
     float* po = part_o + (pidx * kTQ + qq) * kHD + s4;
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj)
@@ -436,19 +440,20 @@ int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const fl
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
     attr_set = true;
   }
-  const int splits = attn_splits(B, g.n_heads, max_prefix, qkv != nullptr);
-  MDZ_REQUIRE(scratch_bytes >= attn_mfma_scratch_bytes(B, g.n_heads, max_prefix), MDZ_EWORKSPACE,
+  const int nq = q_heads(g);
+  const int splits = attn_splits(B, nq, max_prefix, qkv != nullptr);
+  MDZ_REQUIRE(scratch_bytes >= attn_mfma_scratch_bytes(B, nq, max_prefix), MDZ_EWORKSPACE,
               "attention: scratch too small");
   float* part_o = (float*)scratch;
-  float* part_ml = part_o + (int64_t)B * g.n_heads * splits * kTQ * kHD;
-  dim3 grid(splits, g.n_heads, B);
+  float* part_ml = part_o + (int64_t)B * nq * splits * kTQ * kHD;
+  dim3 grid(splits, nq, B);
   const Partials none = single_slot(nullptr, 0, 0);
   attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, qkv ? *qkv : none, cs, g, (bf16_t*)kc,
                                                           (bf16_t*)vc, layer, seq_len, max_prefix, (bf16_t*)att_out,
                                                           part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_combine_kernel<<<dim3(g.n_heads, B, kTQ / 16), 256, 0, st>>>(g.n_heads, splits, part_o, part_ml, (bf16_t*)att_out);
+    attn_combine_kernel<<<dim3(nq, B, kTQ / 16), 256, 0, st>>>(nq, splits, part_o, part_ml, (bf16_t*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;

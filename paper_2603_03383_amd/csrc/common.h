@@ -120,9 +120,11 @@ struct Packed<float> {
 //     order in which the score MFMA leaves its 16 keys per lane, so probabilities feed the second MFMA
 //     straight from registers.
 struct KvGeom {
-  int n_layers, batch, n_heads, head_dim, cap;
+  int n_layers, batch, n_heads, head_dim, cap;  // n_heads: key/value heads (the heads the cache holds)
   int tiled;  // 1: bf16 block layout above (head_dim % 32 == 0); 0: plain
+  int group;  // query heads per key/value head (grouped-query attention; 1: plain multi-head attention)
 };
+__host__ __device__ inline int q_heads(const KvGeom& g) { return g.n_heads * g.group; }
 __host__ __device__ inline int kv_cap_pad(const KvGeom& g) { return g.tiled ? (g.cap + 31) & ~31 : g.cap; }
 __host__ __device__ inline int64_t kv_head_base(const KvGeom& g, int l, int b, int h) {
   return (((int64_t)l * g.batch + b) * g.n_heads + h) * (int64_t)kv_cap_pad(g) * g.head_dim;

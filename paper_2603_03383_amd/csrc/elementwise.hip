@@ -154,7 +154,9 @@ int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, i
   return MDZ_OK;
 }
 
-// grid (B*T, n_heads), block = head_dim/2 threads... generalised: threads stride over i < half.
+// grid (B*T, query heads), block = head_dim/2 threads... generalised: threads stride over i < half.  The QKV GEMM
+// output has the query heads' columns first, then the key heads', then the value heads'; the first query head of a
+// group also rotates and stores its group's key row and stores its value row.
 template <typename T>
 __global__ void rope_kvwrite_kernel(int tree, Partials part, const float* __restrict__ cs,
                                     T* __restrict__ q_out, KvGeom g, T* __restrict__ kc, T* __restrict__ vc, int layer,
@@ -163,33 +165,37 @@ __global__ void rope_kvwrite_kernel(int tree, Partials part, const float* __rest
   int row = blockIdx.x;  // b*T + n
   int h = blockIdx.y;
   int b = row / t.T, n = row % t.T;
-  int hd = g.head_dim, half = hd / 2, d = g.n_heads * hd;
+  int hd = g.head_dim, half = hd / 2, dq = q_heads(g) * hd, dkv = g.n_heads * hd;
   int S = min(max(seq_len[b], 0), max_prefix);
   int slot = S + n;
-  const float* qr = part.p + (int64_t)row * 3 * d;
-  auto rd = [&](int c) {  // fixed-order sum of the partial-sum slots of column h*hd + c
-    const int col = h * hd + c;
+  const float* qr = part.p + (int64_t)row * part.ld;
+  auto rd = [&](int col) {  // fixed-order sum of the partial-sum slots of one column
     const int n_part = part.count(col);
     float v = 0.f;
     for (int p = 0; p < n_part; ++p) v += qr[(int64_t)p * part.stride + col];
     return v;
   };
+  const bool leader = h % g.group == 0;
+  const int hk = h / g.group;
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
     float c = cs[((int64_t)row * half + i) * 2], s = cs[((int64_t)row * half + i) * 2 + 1];
-    float qa = rd(i), qb = rd(i + half);
-    float ka = rd(d + i), kb = rd(d + i + half);
-    float va = rd(2 * d + i), vb = rd(2 * d + i + half);
-    q_out[(int64_t)row * d + h * hd + i] = from_float<T>(qa * c - qb * s);
-    q_out[(int64_t)row * d + h * hd + i + half] = from_float<T>(qb * c + qa * s);
-    kc[k_index(g, layer, b, h, slot, i)] = from_float<T>(ka * c - kb * s);
-    kc[k_index(g, layer, b, h, slot, i + half)] = from_float<T>(kb * c + ka * s);
-    vc[v_index(g, layer, b, h, slot, i)] = from_float<T>(va);
-    vc[v_index(g, layer, b, h, slot, i + half)] = from_float<T>(vb);
+    float qa = rd(h * hd + i), qb = rd(h * hd + i + half);
+    q_out[(int64_t)row * dq + h * hd + i] = from_float<T>(qa * c - qb * s);
+    q_out[(int64_t)row * dq + h * hd + i + half] = from_float<T>(qb * c + qa * s);
+    if (leader) {
+      float ka = rd(dq + hk * hd + i), kb = rd(dq + hk * hd + i + half);
+      float va = rd(dq + dkv + hk * hd + i), vb = rd(dq + dkv + hk * hd + i + half);
+      kc[k_index(g, layer, b, hk, slot, i)] = from_float<T>(ka * c - kb * s);
+      kc[k_index(g, layer, b, hk, slot, i + half)] = from_float<T>(kb * c + ka * s);
+      vc[v_index(g, layer, b, hk, slot, i)] = from_float<T>(va);
+      vc[v_index(g, layer, b, hk, slot, i + half)] = from_float<T>(vb);
+    }
   }
 }
 
 // bf16 / head_dim 128 / tiled cache: one thread per (head, matrix, 4 rotary pairs), all partial-sum slots of its
-// two float4 in flight at once.  grid (rows, n_heads / 4), 192 threads.
+// two float4 in flight at once.  grid (rows, query heads / 4), 192 threads; the key / value threads of a query head
+// that does not lead its group have nothing to do.
 constexpr int kMaxSlots = 8;
 __device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
   return uint2{(uint32_t)float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16),
@@ -204,11 +210,13 @@ __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partial
   const int row = blockIdx.x, h = blockIdx.y * 4 + threadIdx.x / 48, w = threadIdx.x % 48;
   const int which = w / 16, i = (w % 16) * 4;  // matrix (q,k,v) and first of 4 features; partner at i + 64
   const int b = row / t.T, n = row % t.T;
-  const int d = g.n_heads * 128;
+  const int dq = q_heads(g) * 128, dkv = g.n_heads * 128;
   const int S = min(max(seq_len[b], 0), max_prefix);
   const int slot = S + n;
-  const int col = which * d + h * 128 + i;
-  const float* src = part.p + (int64_t)row * 3 * d + col;
+  const int hk = h / g.group;
+  if (which != 0 && h % g.group != 0) return;
+  const int col = (which == 0 ? h * 128 : which == 1 ? dq + hk * 128 : dq + dkv + hk * 128) + i;
+  const float* src = part.p + (int64_t)row * part.ld + col;
   const int n_part = part.count(col);
   float4 lo[kMaxSlots], hi[kMaxSlots];
 #pragma unroll
@@ -230,8 +238,8 @@ __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partial
     const float va[4] = {a.x, a.y, a.z, a.w}, vb[4] = {bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      vc[v_index(g, layer, b, h, slot, i + e)] = float_to_bf16(va[e]);
-      vc[v_index(g, layer, b, h, slot, i + 64 + e)] = float_to_bf16(vb[e]);
+      vc[v_index(g, layer, b, hk, slot, i + e)] = float_to_bf16(va[e]);
+      vc[v_index(g, layer, b, hk, slot, i + 64 + e)] = float_to_bf16(vb[e]);
     }
     return;
   }
@@ -240,12 +248,12 @@ __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partial
   const uint2 rhi = pack_bf16x4(bq.x * c01.x + a.x * c01.y, bq.y * c01.z + a.y * c01.w, bq.z * c23.x + a.z * c23.y,
                                 bq.w * c23.z + a.w * c23.w);
   if (which == 0) {
-    bf16_t* qo = q_out + (int64_t)row * d + h * 128 + i;
+    bf16_t* qo = q_out + (int64_t)row * dq + h * 128 + i;
     *reinterpret_cast<uint2*>(qo) = rlo;
     *reinterpret_cast<uint2*>(qo + 64) = rhi;
   } else {  // 4 consecutive features of one key are 8 contiguous bytes of the tiled K layout
-    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, h, slot, i)) = rlo;
-    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, h, slot, i + 64)) = rhi;
+    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, hk, slot, i)) = rlo;
+    *reinterpret_cast<uint2*>(kc + k_index(g, layer, b, hk, slot, i + 64)) = rhi;
   }
 }
 
@@ -255,11 +263,11 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   ProfScope prof_(PROF_ROPE, st);
   const TreeTables* t = host_tree(tree);
   if (B == 0) return MDZ_OK;
-  dim3 grid(B * t->T, g.n_heads);
+  dim3 grid(B * t->T, q_heads(g));
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
-  if (dtype == MDZ_BF16 && g.tiled && g.head_dim == 128 && g.n_heads % 4 == 0 && qkv.n <= kMaxSlots &&
+  if (dtype == MDZ_BF16 && g.tiled && g.head_dim == 128 && q_heads(g) % 4 == 0 && qkv.n <= kMaxSlots &&
       qkv.stride % 4 == 0 && (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
-    rope_kvwrite_vec_kernel<<<dim3(B * t->T, g.n_heads / 4), 192, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc,
+    rope_kvwrite_vec_kernel<<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc,
                                                                           (bf16_t*)vc, layer, seq_len, max_prefix);
   else if (dtype == MDZ_BF16)
     rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,

@@ -79,8 +79,8 @@ int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, cons
                             int64_t scratch_bytes, hipStream_t st);
 
 int64_t tree_attention_scratch_bytes(int dtype, int tree, const KvGeom& g, int B, int max_prefix) {
-  if (attn_decode_supported(dtype, tree, g)) return attn_decode_scratch_bytes(B, g.n_heads, max_prefix);
-  return attn_mfma_supported(dtype, tree, g) ? attn_mfma_scratch_bytes(B, g.n_heads, max_prefix) : 0;
+  if (attn_decode_supported(dtype, tree, g)) return attn_decode_scratch_bytes(B, q_heads(g), max_prefix);
+  return attn_mfma_supported(dtype, tree, g) ? attn_mfma_scratch_bytes(B, q_heads(g), max_prefix) : 0;
 }
 
 int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, const void* kc, const void* vc,
@@ -111,6 +111,10 @@ int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float*
 }
 
 // ---- workspace ------------------------------------------------------------------------------------
+// key/value heads of a model (0 in the descriptor: as many as query heads) and the width of its K (or V) projection
+static int kv_heads(const mdz_model_desc& m) { return m.n_kv_heads > 0 ? m.n_kv_heads : m.n_heads; }
+static int kv_width(const mdz_model_desc& m) { return kv_heads(m) * m.head_dim; }
+
 struct Workspace {
   int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, sel, sel_bytes, attn_scratch, total;
 };
@@ -133,7 +137,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.xn = take(rows * m.d * es);
   {
     int64_t layer_part = 0;
-    const int shapes[4][2] = {{3 * m.d, m.d}, {m.d, m.d}, {2 * m.ffn, m.d}, {m.d, m.ffn}};
+    const int shapes[4][2] = {{m.d + 2 * kv_width(m), m.d}, {m.d, m.d}, {2 * m.ffn, m.d}, {m.d, m.ffn}};
     for (auto& sh : shapes) {
       int64_t e = gemm_part_elems(m.dtype, (int)rows, sh[0], sh[1]) * 4;
       layer_part = e > layer_part ? e : layer_part;
@@ -150,7 +154,8 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
   w.sel_bytes = topk_scratch_bytes((int)rows > B ? (int)rows : B, 16);
   w.sel = take(w.sel_bytes);
-  KvGeom g{m.n_layers, B, m.n_heads, m.head_dim, max_prefix + t->T, (m.dtype == MDZ_BF16 && m.head_dim % 32 == 0) ? 1 : 0};
+  KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (m.dtype == MDZ_BF16 && m.head_dim % 32 == 0) ? 1 : 0,
+           m.n_heads / kv_heads(m)};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
   w.total = off;
   return w;
@@ -162,6 +167,8 @@ static int check_model(const mdz_model_desc* m) {
   MDZ_REQUIRE(host_tree(m->tree) != nullptr, MDZ_EINVAL, "bad tree id %d", m->tree);
   MDZ_REQUIRE(m->d > 0 && m->n_heads > 0 && m->head_dim > 0 && m->ffn > 0 && m->vocab > 0 && m->n_layers > 0,
               MDZ_EINVAL, "model sizes must be positive");
+  MDZ_REQUIRE(m->n_kv_heads >= 0 && m->n_heads % kv_heads(*m) == 0, MDZ_ESHAPE,
+              "n_kv_heads %d does not divide n_heads %d", m->n_kv_heads, m->n_heads);
   MDZ_REQUIRE(m->d == m->n_heads * m->head_dim, MDZ_ESHAPE, "d %d != n_heads %d * head_dim %d", m->d, m->n_heads,
               m->head_dim);
   MDZ_REQUIRE(m->head_dim % 2 == 0, MDZ_ESHAPE, "head_dim %d must be even (rotary pairs)", m->head_dim);
@@ -180,19 +187,20 @@ static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int m
   MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
               "kv sizes must be positive");
   if (m) {
-    MDZ_REQUIRE(kv->dtype == m->dtype && kv->n_heads == m->n_heads && kv->head_dim == m->head_dim &&
+    MDZ_REQUIRE(kv->dtype == m->dtype && kv->n_heads == kv_heads(*m) && kv->head_dim == m->head_dim &&
                     kv->n_layers >= m->n_layers,
                 MDZ_ESHAPE, "kv cache (L%d H%d hd%d dtype%d) does not match the model (L%d H%d hd%d dtype%d)",
-                kv->n_layers, kv->n_heads, kv->head_dim, kv->dtype, m->n_layers, m->n_heads, m->head_dim, m->dtype);
+                kv->n_layers, kv->n_heads, kv->head_dim, kv->dtype, m->n_layers, kv_heads(*m), m->head_dim, m->dtype);
   }
   MDZ_REQUIRE(B >= 0 && B <= kv->batch, MDZ_ESHAPE, "B %d exceeds kv batch %d", B, kv->batch);
   MDZ_REQUIRE(max_prefix >= 0, MDZ_EINVAL, "max_prefix %d < 0", max_prefix);
   return MDZ_OK;
 }
 
-static KvGeom geom(const mdz_kv_desc* kv) {
+// group: query heads per key/value head (1 where only the cache itself is touched)
+static KvGeom geom(const mdz_kv_desc* kv, int group = 1) {
   return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap,
-                (kv->dtype == MDZ_BF16 && kv->head_dim % 32 == 0) ? 1 : 0};
+                (kv->dtype == MDZ_BF16 && kv->head_dim % 32 == 0) ? 1 : 0, group};
 }
 
 // One decoder layer over rows = B*T rows of x.  On entry ws.xn holds RMSNorm(x; g_attn of this layer).  The
@@ -204,7 +212,7 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   const TreeTables* t = host_tree(m.tree);
   const int rows = B * t->T;
   const int ms = max_split_for(rows);
-  const KvGeom g = geom(kv);
+  const KvGeom g = geom(kv, m.n_heads / kv_heads(m));
   int rc;
   float* cs = (float*)(ws + w.rope_cs);
   void* xn = ws + w.xn;
@@ -213,7 +221,8 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   void* att = ws + w.att;
   void* u = ws + w.u;
   Partials pr;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, 3 * m.d, m.d, 3 * m.d, ms, &pr, st))) return rc;
+  const int qkv_cols = m.d + 2 * kv_width(m);
+  if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, qkv_cols, m.d, qkv_cols, ms, &pr, st))) return rc;
   if ((rc = launch_rope_attention(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
                                   ws + w.attn_scratch, w.total - w.attn_scratch, st)))
     return rc;

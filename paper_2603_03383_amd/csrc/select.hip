@@ -66,17 +66,22 @@ __global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ log
   }
 }
 
-// ---- two-stage variant for long rows: stage 1 finds the top-k of each of kSelChunks column chunks (elements
-// held in registers), stage 2 merges the kSelChunks*k candidates.  The top-k of the union of per-chunk top-k
+// ---- two-stage variant for long rows: stage 1 finds the top-k of each of n_chunks column chunks (elements
+// held in registers; n_chunks = 64, or more for rows longer than 131072), stage 2 merges the n_chunks*k candidates.  The top-k of the union of per-chunk top-k
 // lists is the global top-k, and the order is total, so the result equals the single-stage kernel's.
-constexpr int kSelChunks = 64;
-constexpr int kSelPerThread = 8;  // stage 1 covers chunks of up to 256*8 = 2048 columns
+constexpr int kSelChunks = 64;      // chunks per row, at least
+constexpr int kSelMaxChunks = 256;  // and at most: rows of up to 524288 columns
+constexpr int kSelPerThread = 8;    // stage 1 covers chunks of up to 256*8 = 2048 columns
+static int sel_chunks(int V) {
+  const int need = (V + 256 * kSelPerThread - 1) / (256 * kSelPerThread);
+  return need > kSelChunks ? need : kSelChunks;
+}
 
 __global__ void __launch_bounds__(256) topk_stage1_kernel(const float* __restrict__ logits, int V, int64_t ld, int k,
                                                           float* __restrict__ cand_v, int32_t* __restrict__ cand_i) {
   __shared__ Best red[4];
-  const int chunk = blockIdx.x, row = blockIdx.y;
-  const int per = (V + kSelChunks - 1) / kSelChunks;
+  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
+  const int per = (V + n_chunks - 1) / n_chunks;
   const int c0 = chunk * per, c1 = min(c0 + per, V);
   const float* src = logits + (int64_t)row * ld;
   float v[kSelPerThread];
@@ -100,7 +105,7 @@ __global__ void __launch_bounds__(256) topk_stage1_kernel(const float* __restric
     }
     b = block_best_256(b, red);
     if (threadIdx.x == 0) {
-      int64_t o = ((int64_t)row * kSelChunks + chunk) * k + p;
+      int64_t o = ((int64_t)row * n_chunks + chunk) * k + p;
       cand_v[o] = b.v;
       cand_i[o] = b.i;
     }
@@ -110,11 +115,11 @@ __global__ void __launch_bounds__(256) topk_stage1_kernel(const float* __restric
 }
 
 __global__ void __launch_bounds__(256) topk_stage2_kernel(const float* __restrict__ cand_v,
-                                                          const int32_t* __restrict__ cand_i, int k,
+                                                          const int32_t* __restrict__ cand_i, int k, int n_chunks,
                                                           int32_t* __restrict__ out, int64_t out_ld) {
   __shared__ Best red[4];
   const int row = blockIdx.x;
-  const int n = kSelChunks * k;  // <= 640 candidates
+  const int n = n_chunks * k;
   const float* cv = cand_v + (int64_t)row * n;
   const int32_t* ci = cand_i + (int64_t)row * n;
   float pv = INFINITY;
@@ -137,19 +142,20 @@ __global__ void __launch_bounds__(256) topk_stage2_kernel(const float* __restric
   }
 }
 
-int64_t topk_scratch_bytes(int rows, int k) { return (int64_t)rows * kSelChunks * k * 8; }
+// (sized for the largest chunk count, so it does not depend on the row length)
+int64_t topk_scratch_bytes(int rows, int k) { return (int64_t)rows * kSelMaxChunks * k * 8; }
 
 int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld, void* scratch,
                 int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_SELECT, st);
   if (rows == 0 || k == 0) return MDZ_OK;
-  const int per = (V + kSelChunks - 1) / kSelChunks;
-  if (V >= 8192 && per <= 256 * kSelPerThread && scratch && scratch_bytes >= topk_scratch_bytes(rows, k)) {
+  const int n_chunks = sel_chunks(V);
+  if (V >= 8192 && n_chunks <= kSelMaxChunks && scratch && scratch_bytes >= topk_scratch_bytes(rows, k)) {
     float* cv = (float*)scratch;
-    int32_t* ci = (int32_t*)(cv + (int64_t)rows * kSelChunks * k);
-    topk_stage1_kernel<<<dim3(kSelChunks, rows), 256, 0, st>>>(logits, V, ld, k, cv, ci);
+    int32_t* ci = (int32_t*)(cv + (int64_t)rows * n_chunks * k);
+    topk_stage1_kernel<<<dim3(n_chunks, rows), 256, 0, st>>>(logits, V, ld, k, cv, ci);
     MDZ_LAUNCH_CHECK();
-    topk_stage2_kernel<<<rows, 256, 0, st>>>(cv, ci, k, out, out_ld);
+    topk_stage2_kernel<<<rows, 256, 0, st>>>(cv, ci, k, n_chunks, out, out_ld);
   } else {
     topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
   }

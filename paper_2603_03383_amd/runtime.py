@@ -20,10 +20,11 @@ def torch_dtype(dtype: int):
 class DeviceModel:
     """Packed weights of one decoder (+ Medusa heads) on one GPU."""
 
-    def __init__(self, *, d, n_heads, head_dim, ffn, vocab, n_layers, dtype: str, tree: str, rms_eps=1e-5,
+    def __init__(self, *, d, n_heads, head_dim, ffn, vocab, n_layers, dtype: str, tree: str, n_kv_heads: int = 0, rms_eps=1e-5,
                  rope_base=10000.0, device="cuda:0"):
         self.desc = B.ModelDesc(d, n_heads, head_dim, ffn, vocab, n_layers, B.DTYPES[dtype], B.TREES[tree], rms_eps,
-                                rope_base)
+                                rope_base, n_kv_heads)
+        self.kv_heads = n_kv_heads or n_heads
         self.device = torch.device(device)
         self.dtype = B.DTYPES[dtype]
         self.tdtype = torch_dtype(self.dtype)
@@ -113,7 +114,7 @@ class DeviceModel:
         other = copy.copy(self)
         d = self.desc
         other.desc = B.ModelDesc(d.d, d.n_heads, d.head_dim, d.ffn, d.vocab, d.n_layers, d.dtype, B.TREES[tree],
-                                 d.rms_eps, d.rope_base)
+                                 d.rms_eps, d.rope_base, d.n_kv_heads)
         other.tree = B.TREES[tree]
         other.tree_info = B.medusa_tree_info(other.tree)
         keep = len(self._heads) if other.tree_info["K"] == len(self._heads) else 0
@@ -135,7 +136,7 @@ class DeviceKV:
     def __init__(self, model: DeviceModel, batch: int, cap: int, n_layers: Optional[int] = None):
         d = model.desc
         self.model = model
-        self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, d.n_heads, d.head_dim, cap, model.dtype)
+        self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, model.kv_heads, d.head_dim, cap, model.dtype)
         nbytes = B.medusa_kv_bytes(self.desc)
         self.k = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
         self.v = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
@@ -143,7 +144,7 @@ class DeviceKV:
         self.bytes = 2 * nbytes
 
     def write(self, layer: int, seq: int, pos0: int, k_rows: torch.Tensor, v_rows: torch.Tensor) -> None:
-        """k_rows, v_rows: [n_heads, n, head_dim] storage dtype."""
+        """k_rows, v_rows: [key/value heads, n, head_dim] storage dtype."""
         k_rows = k_rows.to(self.model.device, self.model.tdtype).contiguous()
         v_rows = v_rows.to(self.model.device, self.model.tdtype).contiguous()
         B.medusa_kv_write(self.desc, layer, seq, pos0, k_rows.shape[1], k_rows, v_rows)

@@ -180,7 +180,7 @@ def _layer_case(w, S_list, max_prefix, x_seed="layer_x"):
     outs, caches = [], []
     for b, S in enumerate(S_list):
         k, v = W.prefix_kv(w.with_(prefix=tuple(S_list)), 0, b, G.DEV)
-        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc = np.zeros((w.kv_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
         kc[:, :S] = U.to_np(k); vc[:, :S] = U.to_np(v)
         if S:
             kv.write(0, b, 0, k, v)
@@ -396,7 +396,7 @@ def _oracle_step_streamed(w, tokens, S, tree, kv_rows=None):
     for l in range(w.n_layers):
         lw = U.oracle_layer(w, l, device=G.DEV)
         k, v = W.prefix_kv(w, l, 0, G.DEV)
-        kc = np.zeros((w.n_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
+        kc = np.zeros((w.kv_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
         kc[:, :S] = U.to_np(k); vc[:, :S] = U.to_np(v)
         x = O.tree_verify_layer(x, lw, kc, vc, S, tree, cfg)
         if kv_rows is not None and l in kv_rows:

@@ -210,6 +210,12 @@ CONFIGS: Dict[str, Workload] = {
     "cfg4_step_16k": _b7("cfg4_step_16k", 32, (16384,)),
     # 5: 16 ragged sequences, prefix ~ UniformInt[256, 4096]
     "cfg5_ragged_b16": _b7("cfg5_ragged_b16", 32, _ragged_prefixes(BASE_SEED, 16, 256, 4096)),
+    # the paper's own model shape where its Table 1 is readable: 34 layers, 32 query / 8 key-value heads, vocabulary
+    # ~153k (153,600 here: a multiple of 128); its "hidden size 12,800" cannot be the model width of a 7B model and is
+    # read as the FFN width; d = 4096 and head_dim = 128 as in the other configs; bf16 instead of the paper's fp16;
+    # the 64-node tree (4 heads) instead of the paper's 5 heads
+    "next3_paper_shape_1k": Workload(name="next3_paper_shape_1k", dtype="bf16", n_layers=34, d=4096, n_heads=32,
+                                     head_dim=128, ffn=12800, vocab=153600, tree=TREE64, prefix=(1024,), n_kv_heads=8),
 }
 
 
