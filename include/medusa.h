@@ -46,7 +46,7 @@ typedef enum {
 
 /* Compiled-in static trees.  MDZ_TREE_1 is the root alone (T = 1, K = 0): every entry point then computes one
  * ordinary autoregressive decode step, the baseline of the paper's Overhead and Speedup metrics (Section 4.1). */
-typedef enum { MDZ_TREE_15 = 0, MDZ_TREE_64 = 1, MDZ_TREE_1 = 2 } mdz_tree_id;
+typedef enum { MDZ_TREE_15 = 0, MDZ_TREE_64 = 1, MDZ_TREE_1 = 2, MDZ_TREE_64_K5 = 3 /* 64 nodes, five heads */ } mdz_tree_id;
 typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1 } mdz_dtype;
 
 #define MDZ_MAX_HEADS 8

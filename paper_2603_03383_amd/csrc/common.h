@@ -149,6 +149,6 @@ inline int64_t kv_elems(const KvGeom& g) {
 }
 
 // ---- device copies of the trees -----------------------------------------------------------------
-static __constant__ TreeTables c_trees[kNumTrees] = {kTree15, kTree64, kTree1};
+static __constant__ TreeTables c_trees[kNumTrees] = {kTree15, kTree64, kTree1, kTree64K5};
 
 }  // namespace mdz

@@ -10,7 +10,7 @@
 namespace mdz {
 
 constexpr int kMaxT = 64;      // nodes
-constexpr int kMaxK = 4;       // Medusa heads (tree depth)
+constexpr int kMaxK = 5;       // Medusa heads (tree depth)
 constexpr int kMaxPaths = 64;  // leaves
 
 struct TreeTables {
@@ -76,20 +76,23 @@ constexpr TreeTables make_tree(TreeRule rule) {
   return t;
 }
 
-constexpr TreeTables kTree15 = make_tree(TreeRule{3, {2, 2, 2, 0}, {2, 4, 8, 0}});
-constexpr TreeTables kTree64 = make_tree(TreeRule{4, {10, 10, 4, 4}, {10, 12, 4, 3}});
+constexpr TreeTables kTree15 = make_tree(TreeRule{3, {2, 2, 2, 0, 0}, {2, 4, 8, 0, 0}});
+constexpr TreeTables kTree64 = make_tree(TreeRule{4, {10, 10, 4, 4, 0}, {10, 12, 4, 3, 0}});
+// Five heads (the paper's final configuration trains five: Table 2), still 64 nodes: widths 1/9/26/13/9/6, 34 leaves.
+constexpr TreeTables kTree64K5 = make_tree(TreeRule{5, {9, 10, 4, 3, 2}, {9, 10, 4, 3, 2}});
 // The degenerate tree: the root alone (no Medusa head).  A verify step over it is one ordinary autoregressive
 // decode step, the baseline the paper's Overhead and Speedup metrics are defined against (Section 4.1).
-constexpr TreeTables kTree1 = make_tree(TreeRule{0, {0, 0, 0, 0}, {0, 0, 0, 0}});
+constexpr TreeTables kTree1 = make_tree(TreeRule{0, {0, 0, 0, 0, 0}, {0, 0, 0, 0, 0}});
 
 static_assert(kTree15.T == 15 && kTree15.n_paths == 8 && kTree15.n_cand == 7, "15-node tree");
 static_assert(kTree64.T == 64 && kTree64.n_paths == 38 && kTree64.n_cand == 29, "64-node tree");
+static_assert(kTree64K5.T == 64 && kTree64K5.n_paths == 34 && kTree64K5.n_cand == 29, "64-node tree of depth 5");
 static_assert(kTree1.T == 1 && kTree1.n_paths == 1 && kTree1.n_cand == 1 && kTree1.retrieve[0][0] == 0, "single node");
 
-constexpr int kNumTrees = 3;
+constexpr int kNumTrees = 4;
 
 inline const TreeTables* host_tree(int id) {
-  return id == 0 ? &kTree15 : id == 1 ? &kTree64 : id == 2 ? &kTree1 : nullptr;
+  return id == 0 ? &kTree15 : id == 1 ? &kTree64 : id == 2 ? &kTree1 : id == 3 ? &kTree64K5 : nullptr;
 }
 
 }  // namespace mdz

@@ -31,8 +31,9 @@ def test_header_symbols_are_exported():
         assert hasattr(lib, name), name
 
 
-@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64), (W.TREE1, P.MDZ_TREE_1)],
-                         ids=["tree15", "tree64", "tree1"])
+@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64), (W.TREE1, P.MDZ_TREE_1),
+                                      (W.TREE64K5, P.MDZ_TREE_64_K5)],
+                         ids=["tree15", "tree64", "tree1", "tree64k5"])
 def test_compiled_tables_equal_oracle_tree(spec, tid):
     t = P.medusa_tree_tables(tid)
     o = OT.build_tree(spec.caps, spec.budgets)

@@ -14,8 +14,10 @@ from tests.test_gpu_parity import TOL, _i32, _scale, check_argmax_near_tie, _lay
 pytestmark = pytest.mark.gpu
 
 
-def test_tiny_fp32_grouped_heads_full_path():
-    w = W.CONFIGS["cfg1_tiny_fp32"].with_(name="tiny_gqa", n_kv_heads=2)
+@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64K5], ids=lambda s: s.name)
+def test_tiny_fp32_grouped_heads_full_path(spec):
+    """Also the five-head tree (Table 2 trains five heads): heads, verification, acceptance up to depth 5, compaction."""
+    w = W.CONFIGS["cfg1_tiny_fp32"].with_(name="tiny_gqa", n_kv_heads=2, tree=spec)
     S = w.prefix[0]
     tol = TOL["fp32"]
     model = U.oracle_model(w)

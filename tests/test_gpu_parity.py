@@ -57,9 +57,7 @@ def check_topk_near_tie(gpu_ids, gpu_logits, ref_logits, k, tol_abs):
 # config 1: tiny fp32 model, 15-node tree, causal-prefill prefix of 64 tokens — the whole path
 # ------------------------------------------------------------------------------------------------
 
-@pytest.fixture(scope="module")
-def cfg1():
-    w = W.CONFIGS["cfg1_tiny_fp32"]
+def _cfg1_case(w):
     S = w.prefix[0]
     model = U.oracle_model(w)
     tree = U.oracle_tree(w)
@@ -68,6 +66,17 @@ def cfg1():
     lg, hid = O.causal_decode(prefix_tokens, model, kc, vc, 0)
     dm = G.device_model(w)
     return dict(w=w, S=S, model=model, tree=tree, kc=kc, vc=vc, dm=dm, last_hidden=hid[-1], last_logits=lg[-1])
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    return _cfg1_case(W.CONFIGS["cfg1_tiny_fp32"])
+
+
+@pytest.fixture(scope="module")
+def cfg1_k5():
+    """The tiny model under the 64-node tree with five heads (Table 2 trains five heads)."""
+    return _cfg1_case(W.CONFIGS["cfg1_tiny_fp32"].with_(name="tiny_k5", tree=W.TREE64K5))
 
 
 def test_cfg1_heads_verify_accept_compact(cfg1):
@@ -115,6 +124,15 @@ def test_cfg1_heads_verify_accept_compact(cfg1):
 def test_cfg1_planted_acceptance_and_chained_step(cfg1, m):
     """Tree tokens carry the model's own greedy continuation along one path: A must be m+1, the compacted
     cache must equal the oracle's, and a second chained step must agree with the oracle's second step."""
+    _planted_acceptance(cfg1, m)
+
+
+@pytest.mark.parametrize("m", [0, 3, 4, 5])
+def test_five_head_tree_planted_acceptance_up_to_six_tokens(cfg1_k5, m):
+    _planted_acceptance(cfg1_k5, m)
+
+
+def _planted_acceptance(cfg1, m):
     w, S, model, tree, dm = cfg1["w"], cfg1["S"], cfg1["model"], cfg1["tree"], cfg1["dm"]
     T, K = tree["T"], tree["K"]
     tol = TOL["fp32"]
@@ -123,9 +141,7 @@ def test_cfg1_planted_acceptance_and_chained_step(cfg1, m):
     for i in range(K + 1):
         lg1, _ = O.causal_decode([greedy[-1]], model, kg, vg, S + i)
         greedy.append(int(np.argmax(lg1[-1])))
-    path = [0]
-    for d in range(K):
-        path.append(max(n for n in range(T) if tree["parent"][n] == path[-1]))
+    path = [int(n) for n in [r for r in tree["retrieve"] if r[K] >= 0][-1]]      # the last root-to-leaf path of full depth
     tokens = ((np.arange(T) * 37 + 11) % w.vocab).astype(np.int32)
     tokens[0] = greedy[0]
     for d in range(1, m + 1):
@@ -291,7 +307,8 @@ def test_cfg3_shapes_two_layers_full_step_bf16():
 # integer kernels in isolation: bit exact
 # ------------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64)], ids=["tree15", "tree64"])
+@pytest.mark.parametrize("spec,tid", [(W.TREE15, P.MDZ_TREE_15), (W.TREE64, P.MDZ_TREE_64),
+                                      (W.TREE64K5, P.MDZ_TREE_64_K5)], ids=["tree15", "tree64", "tree64k5"])
 @pytest.mark.parametrize("vocab", [2, 3, 5, 1000])
 def test_accept_fuzz_bit_exact(spec, tid, vocab):
     from oracle import tree as OT

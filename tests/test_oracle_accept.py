@@ -76,7 +76,7 @@ def test_exhaustive_on_tiny_trees(caps, budgets, vocab):
     assert n == vocab ** (2 * T)
 
 
-@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64], ids=lambda s: s.name)
+@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64, W.TREE64K5], ids=lambda s: s.name)
 @pytest.mark.parametrize("vocab", [2, 3, 4, 50])
 def test_fuzz_on_static_trees(spec, vocab):
     tree = OT.build_tree(spec.caps, spec.budgets)

@@ -18,14 +18,17 @@ def _tree(spec):
 # tree64: width at depth m = #{(a_1..a_m) : 1 <= a_i <= caps_i, prod a_i <= B_m} with B = (10,12,4,3):
 #   m=1: a <= 10 -> 10;  m=2: sum_{a=1..10} min(10, floor(12/a)) = 10+6+4+3+2+2+1+1+1+1 = 31
 #   m=3: ordered triples with product <= 4: prod 1:1, 2:3, 3:3, 4:6 -> 13;  m=4: prod <= 3: 1+4+4 = 9
+# tree64k5 (five heads), caps = B = (9,10,4,3,2): m=1: 9;  m=2: sum_{a=1..9} min(10, floor(10/a)) = 10+5+3+2+2+1+1+1+1 = 26
+#   m=3: 13 as above;  m=4: 9 as above;  m=5: ordered 5-tuples with product <= 2: 1 + 5 = 6
 # ones in the mask = sum_n (depth_n + 1).
 EXPECT = {
     "tree15": dict(widths=[1, 2, 4, 8], leaves=8, ones=1 + 2 * 2 + 4 * 3 + 8 * 4),
     "tree64": dict(widths=[1, 10, 31, 13, 9], leaves=38, ones=1 + 10 * 2 + 31 * 3 + 13 * 4 + 9 * 5),
+    "tree64k5": dict(widths=[1, 9, 26, 13, 9, 6], leaves=34, ones=1 + 9 * 2 + 26 * 3 + 13 * 4 + 9 * 5 + 6 * 6),
 }
 
 
-@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64], ids=lambda s: s.name)
+@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64, W.TREE64K5], ids=lambda s: s.name)
 def test_counts_and_shapes(spec):
     t = _tree(spec)
     e = EXPECT[spec.name]
@@ -35,11 +38,11 @@ def test_counts_and_shapes(spec):
     assert t["mask"].shape == (t["T"], t["T"])
     assert t["retrieve"].shape == (e["leaves"], K + 1) == (spec.n_paths, K + 1)
     assert int(t["mask"].sum()) == e["ones"]
-    assert e["ones"] == {"tree15": 49, "tree64": 211}[spec.name]
+    assert e["ones"] == {"tree15": 49, "tree64": 211, "tree64k5": 230}[spec.name]
     assert t["n_cand"] == 1 + sum(spec.caps)
 
 
-@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64], ids=lambda s: s.name)
+@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64, W.TREE64K5], ids=lambda s: s.name)
 def test_mask_is_ancestor_relation(spec):
     """mask == reflexive-transitive closure of the parent relation, computed here by boolean matrix
     powers of the child->parent adjacency (a different route from walking pointers)."""
@@ -65,7 +68,7 @@ def test_mask_is_ancestor_relation(spec):
     assert t["parent"][0] == -1 and t["depth"][0] == 0
 
 
-@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64], ids=lambda s: s.name)
+@pytest.mark.parametrize("spec", [W.TREE15, W.TREE64, W.TREE64K5], ids=lambda s: s.name)
 def test_retrieve_rows_are_root_to_leaf_chains(spec):
     t = _tree(spec)
     T = t["T"]

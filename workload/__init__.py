@@ -142,6 +142,7 @@ class TreeSpec:
 
 TREE15 = TreeSpec("tree15", (2, 2, 2), (2, 4, 8), 15, 8)
 TREE64 = TreeSpec("tree64", (10, 10, 4, 4), (10, 12, 4, 3), 64, 38)
+TREE64K5 = TreeSpec("tree64k5", (9, 10, 4, 3, 2), (9, 10, 4, 3, 2), 64, 34)   # five heads, still 64 nodes
 TREE1 = TreeSpec("tree1", (), (), 1, 1)   # the root alone: one autoregressive decode step
 
 
@@ -213,9 +214,9 @@ CONFIGS: Dict[str, Workload] = {
     # the paper's own model shape where its Table 1 is readable: 34 layers, 32 query / 8 key-value heads, vocabulary
     # ~153k (153,600 here: a multiple of 128); its "hidden size 12,800" cannot be the model width of a 7B model and is
     # read as the FFN width; d = 4096 and head_dim = 128 as in the other configs; bf16 instead of the paper's fp16;
-    # the 64-node tree (4 heads) instead of the paper's 5 heads
+    # five Medusa heads (its Table 2) on a 64-node tree of depth 5
     "next3_paper_shape_1k": Workload(name="next3_paper_shape_1k", dtype="bf16", n_layers=34, d=4096, n_heads=32,
-                                     head_dim=128, ffn=12800, vocab=153600, tree=TREE64, prefix=(1024,), n_kv_heads=8),
+                                     head_dim=128, ffn=12800, vocab=153600, tree=TREE64K5, prefix=(1024,), n_kv_heads=8),
 }
 
 
