@@ -48,12 +48,15 @@ F64 = np.float64
 # ----------------------------------------------------------------------------
 
 def round_to_storage(a, dtype: str):
-    """Round float64 values to the nearest (ties-to-even) bf16 / fp32 value, returned as float64."""
+    """Round float64 values to the nearest (ties-to-even) bf16 / fp16 / fp32 value, returned as float64.
+    fp16 is the paper's inference precision (Section 4.1): IEEE binary16, 11 significant bits, subnormals below 2**-14."""
     a = np.asarray(a, dtype=F64)
     if dtype == "fp64":                    # used only by pins that compare against float64 library ops
         return a
     if dtype == "fp32":
         return a.astype(np.float32).astype(F64)
+    if dtype == "fp16":
+        return a.astype(np.float16).astype(F64)
     if dtype == "bf16":
         m, e = np.frexp(a)                 # a = m * 2**e, 0.5 <= |m| < 1
         return np.ldexp(np.rint(m * 256.0), e - 8)   # 8 significant bits, rint = half-to-even

@@ -175,6 +175,21 @@ def test_round_to_storage_matches_torch_casts():
     assert O.round_to_storage(np.array([1.00390625, 1.01171875]), "bf16").tolist() == [1.0, 1.015625]
 
 
+def test_round_to_fp16_binary16_grid_ties_subnormals_and_torch_cast():
+    """fp16 (the paper's precision, Section 4.1): the result lies on the binary16 grid (11 significant bits above
+    2^-14, multiples of 2^-24 below), is a nearest grid point, ties go to even; cross-checked with torch's cast."""
+    x = np.concatenate([W.normal(6, "rnd16", (20000,)).numpy().astype(np.float64) * s for s in (1e-6, 1e-3, 1.0, 300.0)])
+    r = O.round_to_storage(x, "fp16")
+    np.testing.assert_array_equal(r, torch.tensor(x).to(torch.float16).to(torch.float64).numpy())
+    # grid spacing at |x|: 2^(floor(log2|x|) - 10), at least 2^-24; the rounded value is a multiple of it within half a step
+    e = np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -14)))
+    step = 2.0 ** (e - 10)
+    assert np.all(np.abs(r - x) <= step / 2) and np.all(r / step == np.rint(r / step))
+    # ties to even: 1 + 2^-11 -> 1 ; 1 + 3*2^-11 -> 1 + 2^-9 ; 2^-25 -> 0 ; 3*2^-25 -> 2^-23
+    t = np.array([1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 2.0 ** -25, 3 * 2.0 ** -25, 65504.0, -2049.0])
+    assert O.round_to_storage(t, "fp16").tolist() == [1.0, 1 + 2.0 ** -9, 0.0, 2.0 ** -23, 65504.0, -2048.0]
+
+
 # ---------------------------------------------------------------- Medusa heads (O-2)
 
 def test_heads_reduce_to_lm_head_when_w1_is_zero(tiny):
