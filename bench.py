@@ -32,7 +32,7 @@ TRAFFIC_W64 = {"fetch_bytes_per_launch": 112.50e6, "write_bytes_per_launch": 10.
 def algorithmic_bytes(w, with_heads: bool):
     """Bytes one step must move through HBM: every weight once, the prefix KV once, the T new KV rows
     written and read once, the embedding rows gathered.  Activations (<= 1.4 MB each) are not counted."""
-    es = 2 if w.dtype == "bf16" else 4
+    es = 4 if w.dtype == "fp32" else 2
     T, K = w.tree.n_nodes, w.n_medusa
     kvd = w.kv_heads * w.head_dim
     layer_w = (2 * w.d * w.d + 2 * kvd * w.d + 3 * w.d * w.ffn) * es
@@ -271,7 +271,7 @@ def main():
         ab["gemm"] = ab["weights_layers"]
         ab["gemm_w64"] -= ab["lm_head"]
         ab["total"] = ab["weights_layers"] + ab["kv_prefix"] + ab["kv_tree"]
-    # dominant kernel: gemm_mfma_kernel<4,1,2,128> (every 64-row GEMM launch: 128-column bands, 128-feature stages)
+    # dominant kernel: gemm_mfma_kernel<4,1,2,128,E> (every 64-row GEMM launch: 128-column bands, 128-feature stages)
     gemm = prof.get("gemm_w64", dict(launches=0, total_us=0.0))
     gemm_us_per_step = gemm["total_us"] / args.steps
     gemm_gbps = ab["gemm_w64"] / (gemm_us_per_step * 1e-6) / 1e9 if gemm_us_per_step else 0.0
@@ -289,7 +289,7 @@ def main():
         "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
                 "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
                 "kv_share_of_bytes": (ab["kv_prefix"] + ab["kv_tree"]) / ab["total"]},
-        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head)",
+        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128," + ("f16_t" if w.dtype == "fp16" else "bf16_t") + "> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head)",
                      "bound": "hbm", "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gemm_gbps / HBM_PEAK_GBPS,
                      "traffic": TRAFFIC_W64["fetch_bytes_per_launch"] + TRAFFIC_W64["write_bytes_per_launch"],

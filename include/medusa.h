@@ -12,8 +12,9 @@
  * medusa_last_error() describes the failure.  No exceptions, no aborts.
  *
  * Storage dtype (mdz_model_desc.dtype): the element type of weights, embeddings, norm gains, the
- * KV cache and the `hidden` tensors at the boundary: bf16 or fp32.  The residual stream and all
- * logits are fp32 in both modes.  Token ids, lengths and indices are int32.
+ * KV cache and the `hidden` tensors at the boundary: bf16, fp16 (IEEE binary16, the precision the
+ * paper infers in: Section 4.1) or fp32.  bf16 and fp16 share every layout and kernel.  The residual
+ * stream and all logits are fp32 in every mode.  Token ids, lengths and indices are int32.
  *
  * Static trees (Section 3.2, "Tensorization of Tree Topology"): the candidate tree is fixed at
  * compile time.  Node 0 is the root (the base model's own next token, depth 0); depth k holds
@@ -47,7 +48,7 @@ typedef enum {
 /* Compiled-in static trees.  MDZ_TREE_1 is the root alone (T = 1, K = 0): every entry point then computes one
  * ordinary autoregressive decode step, the baseline of the paper's Overhead and Speedup metrics (Section 4.1). */
 typedef enum { MDZ_TREE_15 = 0, MDZ_TREE_64 = 1, MDZ_TREE_1 = 2, MDZ_TREE_64_K5 = 3 /* 64 nodes, five heads */ } mdz_tree_id;
-typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1 } mdz_dtype;
+typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1, MDZ_FP16 = 2 /* IEEE binary16: same layouts and kernels as bf16 */ } mdz_dtype;
 
 #define MDZ_MAX_HEADS 8
 
@@ -145,7 +146,7 @@ int medusa_stream_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
 /* ---- weight packing (one-time, outside any timed region) ------------------------------------ */
 
-/* Rows per packed tile for a dtype (32 for bf16, 16 for fp32). */
+/* Rows per packed tile for a dtype (32 for bf16 and fp16, 16 for fp32). */
 int medusa_pack_tile_rows(int dtype);
 
 /* Host-only introspection of the weight-streaming GEMM's work decomposition for X[M,K] x W[N,K]^T (bf16, M <= 64,

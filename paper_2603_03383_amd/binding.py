@@ -17,10 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmedusa_hip.so")
 
 MDZ_OK = 0
-MDZ_BF16, MDZ_FP32 = 0, 1
+MDZ_BF16, MDZ_FP32, MDZ_FP16 = 0, 1, 2
 MDZ_TREE_15, MDZ_TREE_64, MDZ_TREE_1, MDZ_TREE_64_K5 = 0, 1, 2, 3
 MDZ_MAX_HEADS = 8
-DTYPES = {"bf16": MDZ_BF16, "fp32": MDZ_FP32}
+DTYPES = {"bf16": MDZ_BF16, "fp32": MDZ_FP32, "fp16": MDZ_FP16}
 TREES = {"tree15": MDZ_TREE_15, "tree64": MDZ_TREE_64, "tree1": MDZ_TREE_1, "tree64k5": MDZ_TREE_64_K5}
 
 

@@ -1,4 +1,4 @@
-// Single-query attention over the tiled bf16 KV cache: the degenerate tree of one node, i.e. one ordinary
+// Single-query attention over the tiled 16-bit (bf16 or fp16) KV cache: the degenerate tree of one node, i.e. one ordinary
 // autoregressive decode step (Section 4.1: the Time_AR that the paper's Overhead and Speedup are measured
 // against).  The node sees the prefix and itself, so the mask is "slot <= S".
 //
@@ -12,7 +12,7 @@
 
 namespace mdz {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4_t u32x4;
 
 namespace {
 constexpr int kHD = 128;
@@ -28,17 +28,19 @@ __device__ inline float half_sum(float v) {
   for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+template <typename E>
 __device__ inline void unpack8(u32x4 v, float (&f)[8]) {
-  f[0] = __uint_as_float(v.x << 16), f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-  f[2] = __uint_as_float(v.y << 16), f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-  f[4] = __uint_as_float(v.z << 16), f[5] = __uint_as_float(v.z & 0xFFFF0000u);
-  f[6] = __uint_as_float(v.w << 16), f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  f[0] = Elem16<E>::lo(v.x), f[1] = Elem16<E>::hi(v.x);
+  f[2] = Elem16<E>::lo(v.y), f[3] = Elem16<E>::hi(v.y);
+  f[4] = Elem16<E>::lo(v.z), f[5] = Elem16<E>::hi(v.z);
+  f[6] = Elem16<E>::lo(v.w), f[7] = Elem16<E>::hi(v.w);
 }
 }  // namespace
 
+template <typename E>
 __global__ void __launch_bounds__(256)
-    attn_decode_kernel(const bf16_t* __restrict__ q, KvGeom g, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
-                       int layer, const int32_t* __restrict__ seq_len, int max_prefix, bf16_t* __restrict__ att_out,
+    attn_decode_kernel(const E* __restrict__ q, KvGeom g, const E* __restrict__ kc, const E* __restrict__ vc,
+                       int layer, const int32_t* __restrict__ seq_len, int max_prefix, E* __restrict__ att_out,
                        float* __restrict__ part_o, float* __restrict__ part_ml) {
   __shared__ float o_lds[4][kHD];
   __shared__ float ml_lds[4][2];
@@ -57,7 +59,7 @@ __global__ void __launch_bounds__(256)
   const u32x4* qp = reinterpret_cast<const u32x4*>(q + (int64_t)b * d + h * kHD);
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    unpack8(qp[2 * ks + half], qf[ks]);
+    unpack8<E>(qp[2 * ks + half], qf[ks]);
 #pragma unroll
     for (int e = 0; e < 8; ++e) qf[ks][e] *= scale_log2;
   }
@@ -78,7 +80,7 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       float kf[8];
-      unpack8(kd[ks], kf);
+      unpack8<E>(kd[ks], kf);
 #pragma unroll
       for (int e = 0; e < 8; ++e) s += qf[ks][e] * kf[e];
     }
@@ -100,7 +102,7 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         float vf[8];
-        unpack8(vd[2 * t + s2], vf);
+        unpack8<E>(vd[2 * t + s2], vf);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[t] += pe[e] * vf[e];
       }
@@ -130,7 +132,7 @@ __global__ void __launch_bounds__(256)
       acc += wt * o_lds[w][f];
     }
     if (n_splits == 1) {
-      att_out[(int64_t)b * d + h * kHD + f] = float_to_bf16(acc / L);
+      att_out[(int64_t)b * d + h * kHD + f] = from_float<E>(acc / L);
     } else {
       const int64_t pidx = (int64_t)(b * q_heads(g) + h) * n_splits + split;
       part_o[pidx * kHD + f] = acc;
@@ -139,9 +141,10 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+template <typename E>
 __global__ void __launch_bounds__(128)
     attn_decode_combine_kernel(int n_heads, int n_splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                               bf16_t* __restrict__ att_out) {
+                               E* __restrict__ att_out) {
   const int h = blockIdx.x, b = blockIdx.y, f = threadIdx.x;
   const int64_t p0 = (int64_t)(b * n_heads + h) * n_splits;
   float M = -INFINITY;
@@ -152,11 +155,11 @@ __global__ void __launch_bounds__(128)
     L += w * part_ml[(p0 + s) * 2 + 1];
     acc += w * part_o[(p0 + s) * kHD + f];
   }
-  att_out[((int64_t)b * n_heads + h) * kHD + f] = float_to_bf16(acc / L);
+  att_out[((int64_t)b * n_heads + h) * kHD + f] = from_float<E>(acc / L);
 }
 
 bool attn_decode_supported(int dtype, int tree, const KvGeom& g) {
-  return dtype == MDZ_BF16 && g.tiled && g.head_dim == kHD && host_tree(tree)->T == 1;
+  return is_16bit(dtype) && g.tiled && g.head_dim == kHD && host_tree(tree)->T == 1;
 }
 
 static int decode_splits(int B, int n_heads, int max_prefix) {
@@ -172,9 +175,10 @@ int64_t attn_decode_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kHD + 2) * 4;
 }
 
-int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
-                            const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
-                            int64_t scratch_bytes, hipStream_t st) {
+template <typename E>
+static int launch_attention_decode_t(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                                     const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                                     int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
   const int nq = q_heads(g);
@@ -183,14 +187,21 @@ int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, cons
               "decode attention: scratch too small");
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (int64_t)B * nq * splits * kHD;
-  attn_decode_kernel<<<dim3(splits, nq, B), 256, 0, st>>>((const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
-                                                                 layer, seq_len, max_prefix, (bf16_t*)att_out, part_o, part_ml);
+  attn_decode_kernel<E><<<dim3(splits, nq, B), 256, 0, st>>>((const E*)q, g, (const E*)kc, (const E*)vc, layer, seq_len,
+                                                             max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_decode_combine_kernel<<<dim3(nq, B), 128, 0, st>>>(nq, splits, part_o, part_ml, (bf16_t*)att_out);
+    attn_decode_combine_kernel<E><<<dim3(nq, B), 128, 0, st>>>(nq, splits, part_o, part_ml, (E*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;
+}
+
+int launch_attention_decode(int dtype, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+                            const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
+                            int64_t scratch_bytes, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_attention_decode_t<E>(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
+                                                             scratch_bytes, st));
 }
 
 }  // namespace mdz

@@ -95,12 +95,8 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
   if (B == 0) return MDZ_OK;
   MDZ_REQUIRE(g.head_dim <= 256, MDZ_EUNSUPPORTED, "attention: head_dim %d > 256", g.head_dim);
   dim3 grid(B * t->T, q_heads(g));
-  if (dtype == MDZ_BF16)
-    attn_generic_kernel<bf16_t><<<grid, 256, 0, st>>>(tree, (const bf16_t*)q, g, (const bf16_t*)kc, (const bf16_t*)vc,
-                                                      layer, seq_len, max_prefix, (bf16_t*)att_out);
-  else
-    attn_generic_kernel<float><<<grid, 256, 0, st>>>(tree, (const float*)q, g, (const float*)kc, (const float*)vc,
-                                                     layer, seq_len, max_prefix, (float*)att_out);
+  MDZ_WITH_ELEM(dtype, (attn_generic_kernel<E><<<grid, 256, 0, st>>>(tree, (const E*)q, g, (const E*)kc, (const E*)vc, layer,
+                                                                     seq_len, max_prefix, (E*)att_out)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

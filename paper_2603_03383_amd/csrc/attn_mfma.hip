@@ -1,4 +1,4 @@
-// Tree-masked attention for bf16 storage, 64-node tree, head_dim 128, on gfx950 MFMA
+// Tree-masked attention for 16-bit storage (bf16 or fp16, element type E), 64-node tree, head_dim 128, on gfx950 MFMA
 // (Section 3.2: all T candidates attend in one pass; node i sees the whole prefix plus the tree slots
 // its row of the static visibility matrix allows).
 //
@@ -7,7 +7,7 @@
 // cache (common.h): each 1 KiB unit is loaded with one contiguous 16-byte-per-lane load and used
 // directly as an MFMA A operand.  Scores are computed transposed (keys x queries), which leaves every
 // lane with 16 keys of ONE query: the running max / sum need a single exchange with lane+32, and the
-// probabilities are packed to bf16 in place as the B operand of the second MFMA (out^T = V^T P^T).
+// probabilities are packed to the storage type in place as the B operand of the second MFMA (out^T = V^T P^T).
 // The tree mask is one 64-bit word per query (a compile-time table) tested only in blocks that reach
 // past the prefix.  Waves merge through LDS, key-splits through a small second kernel, both in a fixed
 // order, so results are deterministic.
@@ -19,9 +19,8 @@
 
 namespace mdz {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef f32x16_t f32x16;
+typedef u32x4_t u32x4;
 
 constexpr int kHD = 128;         // head_dim
 constexpr int kTQ = 64;          // queries (tree nodes)
@@ -31,16 +30,10 @@ constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ inline uint32_t pack_bf16x2(float a, float b) {
-  // round to nearest even, finite non-negative inputs
-  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-  ua += 0x7FFFu + ((ua >> 16) & 1u);
-  ub += 0x7FFFu + ((ub >> 16) & 1u);
-  return (ua >> 16) | (ub & 0xFFFF0000u);
-}
-
-__device__ inline u32x4 pack_bf16x8(const float* v) {
-  return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+template <typename E>
+__device__ inline u32x4 pack8(const float* v) {
+  return u32x4{Elem16<E>::pack2(v[0], v[1]), Elem16<E>::pack2(v[2], v[3]), Elem16<E>::pack2(v[4], v[5]),
+               Elem16<E>::pack2(v[6], v[7])};
 }
 
 // NM head-matrices (q, or q k v, of head h) of the QKV GEMM output for the prologue below: thread (row = t/4,
@@ -99,10 +92,11 @@ __device__ inline void rope16(const float* cs_row, int seg, float (&lo)[16], flo
 // cos/sin table cs [row][64][2]), keeps q in LDS, and — if its key range reaches the tree slots — writes the 64
 // tree rows of K and V of its head into the cache before reading them back like any other key.  Workgroups of
 // the same head that both reach the tree slots write identical values.
+template <typename E>
 __global__ void __launch_bounds__(256)
-    attn_tree_mfma_kernel(int tree, const bf16_t* __restrict__ q, const Partials qkv, const float* __restrict__ cs,
-                          KvGeom g, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int layer,
-                          const int32_t* __restrict__ seq_len, int max_prefix, bf16_t* __restrict__ att_out,
+    attn_tree_mfma_kernel(int tree, const E* __restrict__ q, const Partials qkv, const float* __restrict__ cs,
+                          KvGeom g, E* __restrict__ kc, E* __restrict__ vc, int layer,
+                          const int32_t* __restrict__ seq_len, int max_prefix, E* __restrict__ att_out,
                           float* __restrict__ part_o, float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   const TreeTables& t = c_trees[tree];
@@ -142,10 +136,10 @@ __global__ void __launch_bounds__(256)
     uint8_t* qrow = q_lds + row * kQRow;
     auto stage_q = [&](float (&lo)[16], float (&hi)[16]) {
       rope16(cs_row, seg, lo, hi);
-      *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack_bf16x8(lo);
-      *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack_bf16x8(lo + 8);
-      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack_bf16x8(hi);
-      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack_bf16x8(hi + 8);
+      *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack8<E>(lo);
+      *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack8<E>(lo + 8);
+      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack8<E>(hi);
+      *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack8<E>(hi + 8);
     };
     if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
       // (the query heads of one group all produce their shared key/value rows: identical values, no ordering needed)
@@ -156,14 +150,14 @@ __global__ void __launch_bounds__(256)
       const int slot = S + row;
       rope16(cs_row, seg, lo[1], hi[1]);
       // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack_bf16x8(lo[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack_bf16x8(lo[1] + 8);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack_bf16x8(hi[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack_bf16x8(hi[1] + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack8<E>(lo[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack8<E>(lo[1] + 8);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack8<E>(hi[1]);
+      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack8<E>(hi[1] + 8);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = float_to_bf16(lo[2][i]);
-        vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = float_to_bf16(hi[2][i]);
+        vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = from_float<E>(lo[2][i]);
+        vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = from_float<E>(hi[2][i]);
       }
     } else {
       float lo[1][16], hi[1][16];
@@ -212,11 +206,10 @@ __global__ void __launch_bounds__(256)
       for (int r = 0; r < 16; ++r) sc[u][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      bf16x8 a = __builtin_bit_cast(bf16x8, kd[ks]);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        bf16x8 qv = *reinterpret_cast<const bf16x8*>(qfrag + u * 32 * kQRow + ks * 32);
-        sc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qv, sc[u], 0, 0, 0);
+        const u32x4 qv = *reinterpret_cast<const u32x4*>(qfrag + u * 32 * kQRow + ks * 32);
+        sc[u] = Elem16<E>::mfma(kd[ks], qv, sc[u]);
       }
     }
     // Visibility of this block's 32 keys for the lane's query, as one 32-bit word: prefix keys are
@@ -225,7 +218,7 @@ __global__ void __launch_bounds__(256)
     const int rel0 = blk * 32 - S;
     const bool need_mask = rel0 + 32 > 0;  // wave-uniform: the block reaches past the prefix
     float alpha[2];
-    bf16x8 pf[2][2];
+    u32x4 pf[2][2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       uint32_t vis = 0xFFFFFFFFu;
@@ -252,12 +245,12 @@ __global__ void __launch_bounds__(256)
       for (int r = 0; r < 16; r += 2) {
         float p0 = fast_exp2(sc[u][r] - m_safe), p1 = fast_exp2(sc[u][r + 1] - m_safe);
         sum += p0 + p1;
-        pk[r >> 1] = pack_bf16x2(p0, p1);
+        pk[r >> 1] = Elem16<E>::pack2(p0, p1);
       }
       l_run[u] = l_run[u] * alpha[u] + sum;
       m_run[u] = m_new;
-      pf[u][0] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
-      pf[u][1] = __builtin_bit_cast(bf16x8, u32x4{pk[4], pk[5], pk[6], pk[7]});
+      pf[u][0] = u32x4{pk[0], pk[1], pk[2], pk[3]};
+      pf[u][1] = u32x4{pk[4], pk[5], pk[6], pk[7]};
     }
     if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) {
 #pragma unroll
@@ -271,9 +264,8 @@ __global__ void __launch_bounds__(256)
     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        bf16x8 a = __builtin_bit_cast(bf16x8, vd[tt * 2 + s2]);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) o[tt][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[u][s2], o[tt][u], 0, 0, 0);
+        for (int u = 0; u < 2; ++u) o[tt][u] = Elem16<E>::mfma(vd[tt * 2 + s2], pf[u][s2], o[tt][u]);
       }
   };
 
@@ -341,14 +333,11 @@ __global__ void __launch_bounds__(256)
   }
   if (n_splits == 1) {
     const float inv = 1.0f / L;
-    bf16_t* dst = att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + s4;
+    E* dst = att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + s4;
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      bf16_t v0 = float_to_bf16(acc[4 * jj] * inv), v1 = float_to_bf16(acc[4 * jj + 1] * inv);
-      bf16_t v2 = float_to_bf16(acc[4 * jj + 2] * inv), v3 = float_to_bf16(acc[4 * jj + 3] * inv);
-      *reinterpret_cast<uint2*>(dst + 16 * jj) =
-          uint2{(uint32_t)v0.bits | ((uint32_t)v1.bits << 16), (uint32_t)v2.bits | ((uint32_t)v3.bits << 16)};
-    }
+    for (int jj = 0; jj < 8; ++jj)
+      *reinterpret_cast<uint2*>(dst + 16 * jj) = uint2{Elem16<E>::pack2(acc[4 * jj] * inv, acc[4 * jj + 1] * inv),
+                                                       Elem16<E>::pack2(acc[4 * jj + 2] * inv, acc[4 * jj + 3] * inv)};
   } else {
     const int64_t pidx = ((int64_t)(b * q_heads(g) + h) * n_splits + split);
     float* po = part_o + (pidx * kTQ + qq) * kHD + s4;
@@ -364,9 +353,10 @@ __global__ void __launch_bounds__(256)
 
 // Merges the key-splits of 16 queries of one (sequence, head): fixed order, exact same weighting rule as above.
 // Thread (q = t/16, c = t%16) owns features 8c .. 8c+7 of query 16*blockIdx.z + q.
+template <typename E>
 __global__ void __launch_bounds__(256)
     attn_combine_kernel(int n_heads, int n_splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                        bf16_t* __restrict__ att_out) {
+                        E* __restrict__ att_out) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int d = n_heads * kHD;
   const int qq = blockIdx.z * 16 + (threadIdx.x >> 4), f0 = (threadIdx.x & 15) * 8;
@@ -388,15 +378,12 @@ __global__ void __launch_bounds__(256)
   const float inv = 1.0f / L;
   uint32_t pk[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    bf16_t lo = float_to_bf16(acc[2 * j] * inv), hi = float_to_bf16(acc[2 * j + 1] * inv);
-    pk[j] = (uint32_t)lo.bits | ((uint32_t)hi.bits << 16);
-  }
+  for (int j = 0; j < 4; ++j) pk[j] = Elem16<E>::pack2(acc[2 * j] * inv, acc[2 * j + 1] * inv);
   *reinterpret_cast<u32x4*>(att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + f0) = u32x4{pk[0], pk[1], pk[2], pk[3]};
 }
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
-  return dtype == MDZ_BF16 && g.tiled && g.head_dim == kHD && host_tree(tree)->T == kTQ;
+  return is_16bit(dtype) && g.tiled && g.head_dim == kHD && host_tree(tree)->T == kTQ;
 }
 
 // Key-splits per (sequence, head).  fused: the kernel starts from the QKV partial sums, so one split is the tree
@@ -429,14 +416,15 @@ int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
 }
 
-int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
-                          void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
-                          void* scratch, int64_t scratch_bytes, hipStream_t st) {
+template <typename E>
+static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
+                                   void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                                   void* scratch, int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
   static bool attr_set = false;
   if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel),
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
     attr_set = true;
   }
@@ -448,15 +436,21 @@ int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const fl
   float* part_ml = part_o + (int64_t)B * nq * splits * kTQ * kHD;
   dim3 grid(splits, nq, B);
   const Partials none = single_slot(nullptr, 0, 0);
-  attn_tree_mfma_kernel<<<grid, 256, kAttnLdsBytes, st>>>(tree, (const bf16_t*)q, qkv ? *qkv : none, cs, g, (bf16_t*)kc,
-                                                          (bf16_t*)vc, layer, seq_len, max_prefix, (bf16_t*)att_out,
-                                                          part_o, part_ml);
+  attn_tree_mfma_kernel<E><<<grid, 256, kAttnLdsBytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
+                                                             layer, seq_len, max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_combine_kernel<<<dim3(nq, B, kTQ / 16), 256, 0, st>>>(nq, splits, part_o, part_ml, (bf16_t*)att_out);
+    attn_combine_kernel<E><<<dim3(nq, B, kTQ / 16), 256, 0, st>>>(nq, splits, part_o, part_ml, (E*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;
+}
+
+int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g,
+                          void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
+                          void* scratch, int64_t scratch_bytes, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_attention_mfma_t<E>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
+                                                           att_out, scratch, scratch_bytes, st));
 }
 
 }  // namespace mdz

@@ -65,10 +65,83 @@ __host__ __device__ inline bf16_t from_float<bf16_t>(float f) {
   return float_to_bf16(f);
 }
 
-inline int elem_bytes(int dtype) { return dtype == MDZ_BF16 ? 2 : 4; }
+// IEEE binary16 (the paper's inference precision, Section 4.1)
+struct f16_t {
+  uint16_t bits;
+};
+__host__ __device__ inline float to_float(f16_t v) { return (float)__builtin_bit_cast(_Float16, v.bits); }
+template <>
+__host__ __device__ inline f16_t from_float<f16_t>(float f) {
+  return f16_t{__builtin_bit_cast(uint16_t, (_Float16)f)};  // round to nearest even
+}
+
+inline bool is_16bit(int dtype) { return dtype == MDZ_BF16 || dtype == MDZ_FP16; }
+inline bool dtype_ok(int dtype) { return dtype == MDZ_BF16 || dtype == MDZ_FP32 || dtype == MDZ_FP16; }
+inline int elem_bytes(int dtype) { return is_16bit(dtype) ? 2 : 4; }
+
+// The two 16-bit storage types share every layout (packed weights, tiled KV cache) and every kernel; a kernel
+// template takes the element type E and gets from Elem16<E> the packing of two floats into one 32-bit word, its
+// inverse, and the 32x32x16 MFMA that consumes 8 elements per lane.
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <typename E>
+struct Elem16;
+template <>
+struct Elem16<bf16_t> {
+  __device__ static inline uint32_t pack2(float a, float b) {  // round to nearest even, finite inputs
+    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    ua += 0x7FFFu + ((ua >> 16) & 1u);
+    ub += 0x7FFFu + ((ub >> 16) & 1u);
+    return (ua >> 16) | (ub & 0xFFFF0000u);
+  }
+  __device__ static inline float lo(uint32_t w) { return __uint_as_float(w << 16); }
+  __device__ static inline float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+  __device__ static inline f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+    typedef __bf16 v8 __attribute__((ext_vector_type(8)));
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
+  }
+};
+template <>
+struct Elem16<f16_t> {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  __device__ static inline uint32_t pack2(float a, float b) {
+    return __builtin_bit_cast(uint32_t, h2{(_Float16)a, (_Float16)b});
+  }
+  __device__ static inline float lo(uint32_t w) { return (float)__builtin_bit_cast(h2, w).x; }
+  __device__ static inline float hi(uint32_t w) { return (float)__builtin_bit_cast(h2, w).y; }
+  __device__ static inline f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
+    typedef _Float16 v8 __attribute__((ext_vector_type(8)));
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
+  }
+};
+// runs `body` with E bound to the element type of any storage dtype
+#define MDZ_WITH_ELEM(dtype, body)    \
+  do {                                \
+    if ((dtype) == MDZ_BF16) {        \
+      using E = ::mdz::bf16_t;        \
+      body;                           \
+    } else if ((dtype) == MDZ_FP16) { \
+      using E = ::mdz::f16_t;         \
+      body;                           \
+    } else {                          \
+      using E = float;                \
+      body;                           \
+    }                                 \
+  } while (0)
+// runs `body` with E bound to the element type of a 16-bit dtype
+#define MDZ_WITH_ELEM16(dtype, body) \
+  do {                               \
+    if ((dtype) == MDZ_BF16) {       \
+      using E = ::mdz::bf16_t;       \
+      body;                          \
+    } else {                         \
+      using E = ::mdz::f16_t;        \
+      body;                          \
+    }                                \
+  } while (0)
 
 // ---- packed weight layout ----------------------------------------------------------------------
-// bf16: rows are grouped in tiles of 32 and tiles in bands of 4 (128 output columns); input features in
+// 16-bit types (bf16, fp16; written as bf16 below): rows are grouped in tiles of 32 and tiles in bands of 4 (128 output columns); input features in
 // k-steps of 16 and k-steps in stages of 16 (256 features).  Memory order: [band][stage][tile in band][k-step
 // in stage][lane][8 bf16], where one k-step of one tile is a 1 KiB block of 64 lanes x 8 bf16: lane l holds row
 // (l % 32), features 16*ks + 8*(l / 32) .. +7 — the B-operand order of the 32x32x16 bf16 MFMA.  So a wave loads
@@ -100,6 +173,8 @@ struct Packed<bf16_t> {
   __host__ __device__ static inline int64_t padded_rows(int64_t n) { return round_up(n, kTileRowsBf16 * kBandTiles); }
 };
 template <>
+struct Packed<f16_t> : Packed<bf16_t> {};
+template <>
 struct Packed<float> {
   static constexpr int kTileRows = kTileRowsF32;
   __host__ __device__ static inline int64_t index(int64_t n, int64_t k, int64_t kp) { return n * kp + k; }
@@ -110,7 +185,7 @@ struct Packed<float> {
 // ---- KV cache layout ---------------------------------------------------------------------------
 // The library owns this layout; callers go through medusa_kv_write / medusa_kv_read.
 // fp32: plain [layer][seq][head][slot][feature] for K and V.
-// bf16: per (layer, seq, head) the slots are grouped in blocks of 32; a block is a sequence of 1 KiB
+// bf16 / fp16: per (layer, seq, head) the slots are grouped in blocks of 32; a block is a sequence of 1 KiB
 // units of 64 lanes x 8 bf16, each unit being one MFMA A operand of the attention kernel, so a wave
 // streams K and V with contiguous 16-byte-per-lane loads and no transposition:
 //   K block (scores^T = K Q^T, rows = keys, contraction over features): unit ks holds for lane l

@@ -35,10 +35,7 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
                  hipStream_t st) {
   ProfScope prof_(PROF_EMBED, st);
   if (rows == 0) return MDZ_OK;
-  if (dtype == MDZ_BF16)
-    embed_kernel<bf16_t><<<rows, 256, 0, st>>>((const bf16_t*)embed, tokens, x, d, vocab);
-  else
-    embed_kernel<float><<<rows, 256, 0, st>>>((const float*)embed, tokens, x, d, vocab);
+  MDZ_WITH_ELEM(dtype, (embed_kernel<E><<<rows, 256, 0, st>>>((const E*)embed, tokens, x, d, vocab)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -111,16 +108,10 @@ int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const voi
                             float eps, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
-  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0) {
-    if (dtype == MDZ_BF16)
-      residual_rmsnorm_vec4_kernel<bf16_t><<<rows, 1024, 0, st>>>(x, part, (const bf16_t*)g, (bf16_t*)xn, d, eps);
-    else
-      residual_rmsnorm_vec4_kernel<float><<<rows, 1024, 0, st>>>(x, part, (const float*)g, (float*)xn, d, eps);
-  } else if (dtype == MDZ_BF16) {
-    residual_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(x, part, (const bf16_t*)g, (bf16_t*)xn, d, eps);
-  } else {
-    residual_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(x, part, (const float*)g, (float*)xn, d, eps);
-  }
+  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0)
+    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
+  else
+    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_kernel<E><<<rows, 256, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -193,19 +184,19 @@ __global__ void rope_kvwrite_kernel(int tree, Partials part, const float* __rest
   }
 }
 
-// bf16 / head_dim 128 / tiled cache: one thread per (head, matrix, 4 rotary pairs), all partial-sum slots of its
+// bf16 or fp16 / head_dim 128 / tiled cache: one thread per (head, matrix, 4 rotary pairs), all partial-sum slots of its
 // two float4 in flight at once.  grid (rows, query heads / 4), 192 threads; the key / value threads of a query head
 // that does not lead its group have nothing to do.
 constexpr int kMaxSlots = 8;
-__device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
-  return uint2{(uint32_t)float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16),
-               (uint32_t)float_to_bf16(c).bits | ((uint32_t)float_to_bf16(d).bits << 16)};
+template <typename E>
+__device__ inline uint2 pack4(float a, float b, float c, float d) {
+  return uint2{Elem16<E>::pack2(a, b), Elem16<E>::pack2(c, d)};
 }
+template <typename E>
 __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partials part, const float* __restrict__ cs,
-                                                               bf16_t* __restrict__ q_out, KvGeom g,
-                                                               bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
-                                                               int layer, const int32_t* __restrict__ seq_len,
-                                                               int max_prefix) {
+                                                               E* __restrict__ q_out, KvGeom g, E* __restrict__ kc,
+                                                               E* __restrict__ vc, int layer,
+                                                               const int32_t* __restrict__ seq_len, int max_prefix) {
   const TreeTables& t = c_trees[tree];
   const int row = blockIdx.x, h = blockIdx.y * 4 + threadIdx.x / 48, w = threadIdx.x % 48;
   const int which = w / 16, i = (w % 16) * 4;  // matrix (q,k,v) and first of 4 features; partner at i + 64
@@ -238,17 +229,17 @@ __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partial
     const float va[4] = {a.x, a.y, a.z, a.w}, vb[4] = {bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      vc[v_index(g, layer, b, hk, slot, i + e)] = float_to_bf16(va[e]);
-      vc[v_index(g, layer, b, hk, slot, i + 64 + e)] = float_to_bf16(vb[e]);
+      vc[v_index(g, layer, b, hk, slot, i + e)] = from_float<E>(va[e]);
+      vc[v_index(g, layer, b, hk, slot, i + 64 + e)] = from_float<E>(vb[e]);
     }
     return;
   }
-  const uint2 rlo = pack_bf16x4(a.x * c01.x - bq.x * c01.y, a.y * c01.z - bq.y * c01.w, a.z * c23.x - bq.z * c23.y,
-                                a.w * c23.z - bq.w * c23.w);
-  const uint2 rhi = pack_bf16x4(bq.x * c01.x + a.x * c01.y, bq.y * c01.z + a.y * c01.w, bq.z * c23.x + a.z * c23.y,
-                                bq.w * c23.z + a.w * c23.w);
+  const uint2 rlo = pack4<E>(a.x * c01.x - bq.x * c01.y, a.y * c01.z - bq.y * c01.w, a.z * c23.x - bq.z * c23.y,
+                             a.w * c23.z - bq.w * c23.w);
+  const uint2 rhi = pack4<E>(bq.x * c01.x + a.x * c01.y, bq.y * c01.z + a.y * c01.w, bq.z * c23.x + a.z * c23.y,
+                             bq.w * c23.z + a.w * c23.w);
   if (which == 0) {
-    bf16_t* qo = q_out + (int64_t)row * dq + h * 128 + i;
+    E* qo = q_out + (int64_t)row * dq + h * 128 + i;
     *reinterpret_cast<uint2*>(qo) = rlo;
     *reinterpret_cast<uint2*>(qo + 64) = rhi;
   } else {  // 4 consecutive features of one key are 8 contiguous bytes of the tiled K layout
@@ -265,16 +256,13 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   if (B == 0) return MDZ_OK;
   dim3 grid(B * t->T, q_heads(g));
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
-  if (dtype == MDZ_BF16 && g.tiled && g.head_dim == 128 && q_heads(g) % 4 == 0 && qkv.n <= kMaxSlots &&
+  if (is_16bit(dtype) && g.tiled && g.head_dim == 128 && q_heads(g) % 4 == 0 && qkv.n <= kMaxSlots &&
       qkv.stride % 4 == 0 && (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
-    rope_kvwrite_vec_kernel<<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc,
-                                                                          (bf16_t*)vc, layer, seq_len, max_prefix);
-  else if (dtype == MDZ_BF16)
-    rope_kvwrite_kernel<bf16_t><<<grid, threads, 0, st>>>(tree, qkv, cs, (bf16_t*)q_out, g, (bf16_t*)kc, (bf16_t*)vc,
-                                                          layer, seq_len, max_prefix);
+    MDZ_WITH_ELEM16(dtype, (rope_kvwrite_vec_kernel<E><<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(
+                               tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer, seq_len, max_prefix)));
   else
-    rope_kvwrite_kernel<float><<<grid, threads, 0, st>>>(tree, qkv, cs, (float*)q_out, g, (float*)kc, (float*)vc,
-                                                         layer, seq_len, max_prefix);
+    MDZ_WITH_ELEM(dtype, (rope_kvwrite_kernel<E><<<grid, threads, 0, st>>>(tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer,
+                                                                           seq_len, max_prefix)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -298,8 +286,9 @@ __global__ void swiglu_kernel(Partials part, T* __restrict__ u, int M, int F) {
   u[idx] = from_float<T>(silu_f(gv) * uv);
 }
 
-// bf16: one thread per 4 features, gate and up float4 of every slot in flight at once
-__global__ void __launch_bounds__(256) swiglu_vec_kernel(Partials part, bf16_t* __restrict__ u, int M, int F) {
+// bf16 / fp16: one thread per 4 features, gate and up float4 of every slot in flight at once
+template <typename E>
+__global__ void __launch_bounds__(256) swiglu_vec_kernel(Partials part, E* __restrict__ u, int M, int F) {
   const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (idx >= (int64_t)M * F) return;
   const int f = (int)(idx % F);
@@ -321,7 +310,7 @@ __global__ void __launch_bounds__(256) swiglu_vec_kernel(Partials part, bf16_t* 
       a.x += gt[p].x, a.y += gt[p].y, a.z += gt[p].z, a.w += gt[p].w;
       b.x += up[p].x, b.y += up[p].y, b.z += up[p].z, b.w += up[p].w;
     }
-  *reinterpret_cast<uint2*>(u + idx) = pack_bf16x4(silu_f(a.x) * b.x, silu_f(a.y) * b.y, silu_f(a.z) * b.z, silu_f(a.w) * b.w);
+  *reinterpret_cast<uint2*>(u + idx) = pack4<E>(silu_f(a.x) * b.x, silu_f(a.y) * b.y, silu_f(a.z) * b.z, silu_f(a.w) * b.w);
 }
 
 int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStream_t st) {
@@ -330,12 +319,10 @@ int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStrea
   if (total == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((total + 255) / 256);
   // gate and up tiles of a pair lie in the same band (band widths are multiples of 64), so one count serves both
-  if (dtype == MDZ_BF16 && F % 32 == 0 && gu.n <= kMaxSlots && gu.stride % 4 == 0 && (gu.split_grid == 0 || gu.band_cols % 64 == 0))
-    swiglu_vec_kernel<<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(gu, (bf16_t*)u, M, F);
-  else if (dtype == MDZ_BF16)
-    swiglu_kernel<bf16_t><<<blocks, 256, 0, st>>>(gu, (bf16_t*)u, M, F);
+  if (is_16bit(dtype) && F % 32 == 0 && gu.n <= kMaxSlots && gu.stride % 4 == 0 && (gu.split_grid == 0 || gu.band_cols % 64 == 0))
+    MDZ_WITH_ELEM16(dtype, (swiglu_vec_kernel<E><<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(gu, (E*)u, M, F)));
   else
-    swiglu_kernel<float><<<blocks, 256, 0, st>>>(gu, (float*)u, M, F);
+    MDZ_WITH_ELEM(dtype, (swiglu_kernel<E><<<blocks, 256, 0, st>>>(gu, (E*)u, M, F)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -353,10 +340,7 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
                        hipStream_t st) {
   ProfScope prof_(PROF_MISC, st);
   if (B == 0) return MDZ_OK;
-  if (dtype == MDZ_BF16)
-    gather_rows_kernel<bf16_t><<<B, 256, 0, st>>>((const bf16_t*)hidden, src_row, Tsrc, d, (bf16_t*)h);
-  else
-    gather_rows_kernel<float><<<B, 256, 0, st>>>((const float*)hidden, src_row, Tsrc, d, (float*)h);
+  MDZ_WITH_ELEM(dtype, (gather_rows_kernel<E><<<B, 256, 0, st>>>((const E*)hidden, src_row, Tsrc, d, (E*)h)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -379,10 +363,7 @@ int launch_head_residual(int dtype, const void* h, const Partials& pre, const vo
   int64_t n = (int64_t)B * d;
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
-  if (dtype == MDZ_BF16)
-    head_residual_kernel<bf16_t><<<blocks, 256, 0, st>>>((const bf16_t*)h, pre, (const bf16_t*)b1, (bf16_t*)z, n, d);
-  else
-    head_residual_kernel<float><<<blocks, 256, 0, st>>>((const float*)h, pre, (const float*)b1, (float*)z, n, d);
+  MDZ_WITH_ELEM(dtype, (head_residual_kernel<E><<<blocks, 256, 0, st>>>((const E*)h, pre, (const E*)b1, (E*)z, n, d)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -397,10 +378,7 @@ int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStre
   ProfScope prof_(PROF_MISC, st);
   if (n == 0) return MDZ_OK;
   unsigned blocks = (unsigned)((n + 255) / 256);
-  if (dtype == MDZ_BF16)
-    store_rows_kernel<bf16_t><<<blocks, 256, 0, st>>>(src, (bf16_t*)dst, n);
-  else
-    store_rows_kernel<float><<<blocks, 256, 0, st>>>(src, (float*)dst, n);
+  MDZ_WITH_ELEM(dtype, (store_rows_kernel<E><<<blocks, 256, 0, st>>>(src, (E*)dst, n)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

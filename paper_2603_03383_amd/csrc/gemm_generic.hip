@@ -57,12 +57,8 @@ int launch_gemm_generic(int dtype, const void* X, const void* Wp, float* Y, int 
   ProfScope prof_(PROF_GEMM, st);
   if (M == 0 || N == 0) return MDZ_OK;
   dim3 grid((N + 63) / 64, (M + 63) / 64);
-  if (dtype == MDZ_BF16)
-    gemm_generic_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)X, (const bf16_t*)Wp, Y, M, N, K,
-                                                      Packed<bf16_t>::padded_k(K), ldy, accumulate);
-  else
-    gemm_generic_kernel<float><<<grid, 256, 0, st>>>((const float*)X, (const float*)Wp, Y, M, N, K, K, ldy,
-                                                     accumulate);
+  MDZ_WITH_ELEM(dtype, (gemm_generic_kernel<E><<<grid, 256, 0, st>>>((const E*)X, (const E*)Wp, Y, M, N, K,
+                                                                     Packed<E>::padded_k(K), ldy, accumulate)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

@@ -1,5 +1,5 @@
-// GEMM for many rows (several sequences verified together: M = B * T >= 128): sum_k X[m][k] * W[n][k], bf16 in,
-// fp32 out.  At M = 1024 the layer GEMMs are bound by the matrix cores, not by the weight stream (1024 flop per
+// GEMM for many rows (several sequences verified together: M = B * T >= 128): sum_k X[m][k] * W[n][k], bf16 or fp16
+// in (element type E), fp32 out.  At M = 1024 the layer GEMMs are bound by the matrix cores, not by the weight stream (1024 flop per
 // weight byte against a machine balance of ~312), so this kernel is built around operand reuse:
 //   * a workgroup (4 waves) owns a 128-row x 256-column output tile; a wave owns two 32-column tiles and all 128
 //     rows: 8 accumulator tiles of 32 x 32 (128 accumulator registers; 256 rows would use the whole accumulator
@@ -16,9 +16,8 @@
 
 namespace mdz {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef f32x16_t f32x16;
+typedef u32x4_t u32x4;
 
 namespace {
 constexpr int kBM = 128;                 // rows per workgroup
@@ -31,8 +30,9 @@ constexpr int kXL = kBM * (kCK / 8) / 256;  // 16-byte X loads per thread per st
 constexpr int kLdsBytes = 2 * kBM * kLRow;
 }  // namespace
 
+template <typename E>
 __global__ void __launch_bounds__(256)
-    gemm_large_kernel(const bf16_t* __restrict__ X, int M, int K, const bf16_t* __restrict__ Wp, int n_tiles,
+    gemm_large_kernel(const E* __restrict__ X, int M, int K, const E* __restrict__ Wp, int n_tiles,
                       float* __restrict__ P, int ldp, int64_t part_stride, int stages_per_split, int nb_n, int nb_m) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
   uint8_t(*lds)[kBM * kLRow] = reinterpret_cast<uint8_t(*)[kBM * kLRow]>(lds_raw);
@@ -95,9 +95,9 @@ __global__ void __launch_bounds__(256)
   };
   auto compute = [&](int buf, const u32x4 (&wv)[kNT][kKS]) {
     const uint8_t* base = &lds[buf][(lane & 31) * kLRow + (lane >> 5) * 16];
-    bf16x8 a[2][kBM / 32];
+    u32x4 a[2][kBM / 32];
 #pragma unroll
-    for (int mt = 0; mt < kBM / 32; ++mt) a[0][mt] = *reinterpret_cast<const bf16x8*>(base + mt * 32 * kLRow);
+    for (int mt = 0; mt < kBM / 32; ++mt) a[0][mt] = *reinterpret_cast<const u32x4*>(base + mt * 32 * kLRow);
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
       // the A operands of the next k-step are read from LDS while this k-step's MFMAs run; sched_barrier keeps that
@@ -105,14 +105,14 @@ __global__ void __launch_bounds__(256)
       if (ks + 1 < kKS) {
 #pragma unroll
         for (int mt = 0; mt < kBM / 32; ++mt)
-          a[(ks + 1) & 1][mt] = *reinterpret_cast<const bf16x8*>(base + mt * 32 * kLRow + (ks + 1) * 32);
+          a[(ks + 1) & 1][mt] = *reinterpret_cast<const u32x4*>(base + mt * 32 * kLRow + (ks + 1) * 32);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int mt = 0; mt < kBM / 32; ++mt)
 #pragma unroll
         for (int nt = 0; nt < kNT; ++nt)
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][mt], __builtin_bit_cast(bf16x8, wv[nt][ks]), acc[nt][mt], 0, 0, 0);
+          acc[nt][mt] = Elem16<E>::mfma(a[ks & 1][mt], wv[nt][ks], acc[nt][mt]);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -188,21 +188,22 @@ LargePlan plan_large(int M, int N, int K) {
 }  // namespace
 
 bool gemm_large_supported(int dtype, int M, int N, int K) {
-  return dtype == MDZ_BF16 && M >= 128 && N % 32 == 0 && K % kCK == 0 && K >= kCK && (int64_t)M * N < (int64_t)1 << 31;
+  return is_16bit(dtype) && M >= 128 && N % 32 == 0 && K % kCK == 0 && K >= kCK && (int64_t)M * N < (int64_t)1 << 31;
 }
 
 // partial-sum slots launch_gemm_large will write for this problem (sizes the slot workspace)
 int gemm_large_slots(int M, int N, int K) { return plan_large(M, N, K).ksplit; }
 
-int launch_gemm_large(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                      Partials* res, hipStream_t st) {
+template <typename E>
+static int launch_gemm_large_t(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
+                               int64_t part_stride, Partials* res, hipStream_t st) {
   ProfScope prof_(PROF_GEMM_LARGE, st);
   const LargePlan p = plan_large(M, N, K);
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
   static bool attr_set = false;
   if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_large_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_large_kernel<E>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes));
     attr_set = true;
   }
@@ -212,10 +213,15 @@ int launch_gemm_large(const void* X, const void* Wp, float* P, int M, int N, int
   res->n_stages = 1;
   res->split_units = 0;
   const int groups = (p.nb_n + 7) / 8;  // column blocks per XCD
-  gemm_large_kernel<<<dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st>>>(
-      (const bf16_t*)X, M, K, (const bf16_t*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m);
+  gemm_large_kernel<E><<<dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st>>>(
+      (const E*)X, M, K, (const E*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
+}
+
+int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
+                      int64_t part_stride, Partials* res, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_gemm_large_t<E>(X, Wp, P, M, N, K, ldp, part_stride, res, st));
 }
 
 }  // namespace mdz

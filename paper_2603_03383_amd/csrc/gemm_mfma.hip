@@ -1,8 +1,8 @@
-// Weight-streaming skinny GEMM for bf16 storage on gfx950: sum_k X[m][k] * W[n][k] for M <= 64 rows (the T
+// Weight-streaming skinny GEMM for 16-bit storage (bf16 or fp16, element type E) on gfx950: sum_k X[m][k] * W[n][k] for M <= 64 rows (the T
 // tree nodes of one sequence, or up to 32 batch rows for the Medusa heads).  This kernel moves >95 % of a
 // verify step's bytes (the decoder weights), so it is built around the HBM stream:
 //   * W arrives in the packed order (common.h): every wave-level load is one contiguous 1 KiB block
-//     (16 B per lane) that already is the B operand of v_mfma_f32_32x32x16_bf16 — no LDS, no shuffles.
+//     (16 B per lane) that already is the B operand of v_mfma_f32_32x32x16_bf16 / _f16 — no LDS, no shuffles.
 //   * A wave owns NT tiles of 32 output columns and moves W through a ring of four half K-stages in
 //     registers: three half stages (CK/2 input features each) stay in flight while it multiplies the
 //     fourth, and every load is unconditional so the hardware wait counters let the prefetch overlap
@@ -19,13 +19,12 @@
 
 namespace mdz {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef f32x16_t f32x16;
+typedef u32x4_t u32x4;
 
-template <int WPB, int NT, int MT, int CK>
+template <int WPB, int NT, int MT, int CK, typename E>
 __global__ void __launch_bounds__(WPB * 64)
-    gemm_mfma_kernel(const bf16_t* __restrict__ X, int M, int K, const bf16_t* __restrict__ Wp, int n_tiles,
+    gemm_mfma_kernel(const E* __restrict__ X, int M, int K, const E* __restrict__ Wp, int n_tiles,
                      int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride, int whole_bands) {
   constexpr int ROWS = MT * 32;
   constexpr int KH = CK / 32;                       // MFMA k-steps per half stage
@@ -117,15 +116,13 @@ __global__ void __launch_bounds__(WPB * 64)
     const uint8_t* base = &lds[buf][(lane & 31) * LROW + (lane >> 5) * 16 + hf * KH * 32];
 #pragma unroll
     for (int ks = 0; ks < KH; ++ks) {
-      bf16x8 a[MT];
+      u32x4 a[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) a[mt] = *reinterpret_cast<const bf16x8*>(base + mt * 32 * LROW + ks * 32);
+      for (int mt = 0; mt < MT; ++mt) a[mt] = *reinterpret_cast<const u32x4*>(base + mt * 32 * LROW + ks * 32);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        bf16x8 b = __builtin_bit_cast(bf16x8, wv[nt][ks]);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b, acc[nt][mt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Elem16<E>::mfma(a[mt], wv[nt][ks], acc[nt][mt]);
       }
     }
   };
@@ -273,7 +270,7 @@ static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
 int gemm_mfma_slots(int M, int N, int K, int max_split) { return plan_gemm(M, N, K, max_split).slots; }
 
 bool gemm_mfma_supported(int dtype, int M, int N, int K) {
-  return dtype == MDZ_BF16 && M >= 1 && M <= 64 && N % 32 == 0 && K % 128 == 0 && K >= 128;
+  return is_16bit(dtype) && M >= 1 && M <= 64 && N % 32 == 0 && K % 128 == 0 && K >= 128;
 }
 
 // The decomposition launch_gemm_mfma will use, as the consumers see it (no GPU work): fills the slot-count fields of
@@ -292,8 +289,9 @@ void gemm_mfma_describe(int M, int N, int K, int max_split, Partials* res, int* 
 
 // Writes partial sums into slots of P (slot s at P + s*part_stride, each [M][ldp] fp32) and fills the fields of
 // *res that describe how many slots each band of columns received (one everywhere when max_split <= 1).
-int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                     int max_split, Partials* res, hipStream_t st) {
+template <typename E>
+static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
+                              int max_split, Partials* res, hipStream_t st) {
   GemmPlan p = plan_gemm(M, N, K, max_split);
   ProfScope prof_(p.mt == 2 ? (p.wpb == 4 ? PROF_GEMM_W64 : PROF_GEMM_N64) : (p.wpb == 4 ? PROF_GEMM_W32 : PROF_GEMM_N32),
                   st);
@@ -304,19 +302,19 @@ int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int 
   MDZ_REQUIRE((int64_t)bands * n_stages * p.grid < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: %d x %d units on %d workgroups overflow",
               bands, n_stages, p.grid);
   gemm_mfma_describe(M, N, K, max_split, res, nullptr);
-  const bf16_t* x = (const bf16_t*)X;
-  const bf16_t* w = (const bf16_t*)Wp;
+  const E* x = (const E*)X;
+  const E* w = (const E*)Wp;
 #define MDZ_GEMM_CASE(WPB, NT, MT, CK)                                                                       \
   if (p.wpb == WPB && p.nt == NT && p.mt == MT && p.ck == CK) {                                              \
     constexpr int lds_bytes = 2 * MT * 32 * (CK * 2 + 16);                                                   \
     static bool attr_set = false;                                                                            \
     if (!attr_set) {                                                                                         \
-      MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<WPB, NT, MT, CK>),          \
+      MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<WPB, NT, MT, CK, E>),       \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));                   \
       attr_set = true;                                                                                       \
     }                                                                                                        \
-    gemm_mfma_kernel<WPB, NT, MT, CK><<<p.grid, WPB * 64, lds_bytes, st>>>(x, M, K, w, n_tiles, n_stages, P, \
-                                                                           ldp, part_stride, p.whole);         \
+    gemm_mfma_kernel<WPB, NT, MT, CK, E><<<p.grid, WPB * 64, lds_bytes, st>>>(x, M, K, w, n_tiles, n_stages, P, \
+                                                                              ldp, part_stride, p.whole);      \
   } else
   MDZ_GEMM_CASE(4, 1, 2, 128)
   MDZ_GEMM_CASE(4, 1, 1, 128)
@@ -329,6 +327,11 @@ int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int 
 #undef MDZ_GEMM_CASE
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
+}
+
+int launch_gemm_mfma(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
+                     int64_t part_stride, int max_split, Partials* res, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_gemm_mfma_t<E>(X, Wp, P, M, N, K, ldp, part_stride, max_split, res, st));
 }
 
 }  // namespace mdz

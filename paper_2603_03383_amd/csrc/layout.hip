@@ -20,8 +20,8 @@ __global__ void pack_weight_kernel(const T* __restrict__ src, int64_t n_rows, in
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, hipStream_t st) {
   ProfScope prof_(PROF_MISC, st);
-  const int R = dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
-  const int64_t kp = dtype == MDZ_BF16 ? Packed<bf16_t>::padded_k(k) : k;
+  const int R = is_16bit(dtype) ? kTileRowsBf16 : kTileRowsF32;
+  const int64_t kp = is_16bit(dtype) ? Packed<bf16_t>::padded_k(k) : k;
   const int64_t n_pad = round_up(n_rows, R);
   const int64_t n_tiles = n_pad / R;
   MDZ_REQUIRE(tile_stride >= 1 && tile_offset >= 0, MDZ_EINVAL, "pack: bad tile offset/stride");
@@ -35,7 +35,7 @@ int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
   const int64_t total = n_pad * kp;
   const int threads = 256;
   const int64_t blocks = (total + threads - 1) / threads;
-  if (dtype == MDZ_BF16)
+  if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
     pack_weight_kernel<bf16_t><<<dim3((unsigned)blocks), threads, 0, st>>>(
         (const bf16_t*)src, n_rows, k, (bf16_t*)dst, kp, tile_offset, tile_stride, n_pad);
   else
@@ -73,7 +73,7 @@ int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, in
   int64_t total = (int64_t)g.n_heads * n * g.head_dim;
   int threads = 256;
   unsigned blocks = (unsigned)((total + threads - 1) / threads);
-  if (dtype == MDZ_BF16)
+  if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
     kv_copy_kernel<bf16_t><<<blocks, threads, 0, st>>>(g, (bf16_t*)kc, (bf16_t*)vc, layer, seq, pos0, n,
                                                        (bf16_t*)k_rows, (bf16_t*)v_rows, to_cache);
   else
@@ -133,7 +133,7 @@ int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, 
   int64_t cols = (int64_t)g.n_layers * g.n_heads * g.head_dim;
   int threads = 256;
   dim3 grid((unsigned)((cols + threads - 1) / threads), B);
-  if (dtype == MDZ_BF16)
+  if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
     kv_compact_kernel<bf16_t><<<grid, threads, 0, st>>>(g, (bf16_t*)kc, (bf16_t*)vc, tree, acc_nodes, accept_len,
                                                         seq_len, max_prefix);
   else

@@ -25,28 +25,28 @@ int launch_attention_generic(int dtype, int tree, const void* q, const KvGeom& g
 bool gemm_mfma_supported(int dtype, int M, int N, int K);
 int gemm_mfma_slots(int M, int N, int K, int max_split);
 void gemm_mfma_describe(int M, int N, int K, int max_split, Partials* res, int* grid);
-int launch_gemm_mfma(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                     int max_split, Partials* res, hipStream_t st);
+int launch_gemm_mfma(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
+                     int64_t part_stride, int max_split, Partials* res, hipStream_t st);
 
 bool gemm_large_supported(int dtype, int M, int N, int K);
 int gemm_large_slots(int M, int N, int K);
-int launch_gemm_large(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
-                      Partials* res, hipStream_t st);
+int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
+                      int64_t part_stride, Partials* res, hipStream_t st);
 
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld, int max_split,
                 Partials* res, hipStream_t st) {
   *res = single_slot(out, (int64_t)M * ld, ld);
   // several sequences at once: the MFMA-bound kernel (it splits K only when the caller's consumer reduces slots)
   if (gemm_large_supported(dtype, M, N, K) && (max_split > 1 || gemm_large_slots(M, N, K) == 1))
-    return launch_gemm_large(X, Wp, out, M, N, K, ld, res->stride, res, st);
+    return launch_gemm_large(dtype, X, Wp, out, M, N, K, ld, res->stride, res, st);
   const int rows_per_launch = M <= 64 ? M : 64;
   if (gemm_mfma_supported(dtype, rows_per_launch, N, K) && (M <= 64 || M % 64 == 0)) {
     // More than 64 rows (several sequences): one launch per block of 64 rows.  Every launch uses the same plan, so
     // the slot counts are identical; the first launch streams the matrix from HBM, the following ones mostly from
     // the memory-side cache.
     for (int m0 = 0; m0 < M; m0 += rows_per_launch) {
-      int rc = launch_gemm_mfma((const char*)X + (int64_t)m0 * K * 2, Wp, out + (int64_t)m0 * ld, rows_per_launch, N, K, ld,
-                                res->stride, max_split, res, st);
+      int rc = launch_gemm_mfma(dtype, (const char*)X + (int64_t)m0 * K * 2, Wp, out + (int64_t)m0 * ld, rows_per_launch, N,
+                                K, ld, res->stride, max_split, res, st);
       if (rc) return rc;
     }
     return MDZ_OK;
@@ -68,13 +68,13 @@ static int64_t gemm_part_elems(int dtype, int rows, int N, int K) {
 
 bool attn_mfma_supported(int dtype, int tree, const KvGeom& g);
 int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix);
-int launch_attention_mfma(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
+int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
                           void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                           void* scratch, int64_t scratch_bytes, hipStream_t st);
 
 bool attn_decode_supported(int dtype, int tree, const KvGeom& g);
 int64_t attn_decode_scratch_bytes(int B, int n_heads, int max_prefix);
-int launch_attention_decode(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
+int launch_attention_decode(int dtype, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
                             const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                             int64_t scratch_bytes, hipStream_t st);
 
@@ -87,9 +87,9 @@ int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, c
                           int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                           int64_t scratch_bytes, hipStream_t st) {
   if (attn_decode_supported(dtype, tree, g))
-    return launch_attention_decode(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch, scratch_bytes, st);
+    return launch_attention_decode(dtype, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch, scratch_bytes, st);
   if (attn_mfma_supported(dtype, tree, g))
-    return launch_attention_mfma(tree, q, nullptr, nullptr, g, (void*)kc, (void*)vc, layer, seq_len, B, max_prefix,
+    return launch_attention_mfma(dtype, tree, q, nullptr, nullptr, g, (void*)kc, (void*)vc, layer, seq_len, B, max_prefix,
                                  att_out, scratch, scratch_bytes, st);
   return launch_attention_generic(dtype, tree, q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, st);
 }
@@ -102,7 +102,7 @@ int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float*
   static const bool unfused = getenv("MDZ_UNFUSED_ROPE") != nullptr;  // development knob
   if (!unfused && attn_mfma_supported(dtype, tree, g) && qkv.stride % 4 == 0 && qkv.ld % 4 == 0 &&
       (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
-    return launch_attention_mfma(tree, nullptr, &qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
+    return launch_attention_mfma(dtype, tree, nullptr, &qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
                                  scratch_bytes, st);
   int rc = launch_rope_kvwrite(dtype, tree, qkv, cs, q_scratch, g, kc, vc, layer, seq_len, B, max_prefix, st);
   if (rc) return rc;
@@ -154,7 +154,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
   w.sel_bytes = topk_scratch_bytes((int)rows > B ? (int)rows : B, 16);
   w.sel = take(w.sel_bytes);
-  KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (m.dtype == MDZ_BF16 && m.head_dim % 32 == 0) ? 1 : 0,
+  KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (is_16bit(m.dtype) && m.head_dim % 32 == 0) ? 1 : 0,
            m.n_heads / kv_heads(m)};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
   w.total = off;
@@ -163,7 +163,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
 
 static int check_model(const mdz_model_desc* m) {
   MDZ_REQUIRE(m != nullptr, MDZ_EINVAL, "model descriptor is NULL");
-  MDZ_REQUIRE(m->dtype == MDZ_BF16 || m->dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", m->dtype);
+  MDZ_REQUIRE(dtype_ok(m->dtype), MDZ_EINVAL, "bad dtype %d", m->dtype);
   MDZ_REQUIRE(host_tree(m->tree) != nullptr, MDZ_EINVAL, "bad tree id %d", m->tree);
   MDZ_REQUIRE(m->d > 0 && m->n_heads > 0 && m->head_dim > 0 && m->ffn > 0 && m->vocab > 0 && m->n_layers > 0,
               MDZ_EINVAL, "model sizes must be positive");
@@ -172,18 +172,18 @@ static int check_model(const mdz_model_desc* m) {
   MDZ_REQUIRE(m->d == m->n_heads * m->head_dim, MDZ_ESHAPE, "d %d != n_heads %d * head_dim %d", m->d, m->n_heads,
               m->head_dim);
   MDZ_REQUIRE(m->head_dim % 2 == 0, MDZ_ESHAPE, "head_dim %d must be even (rotary pairs)", m->head_dim);
-  const int R = m->dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
+  const int R = is_16bit(m->dtype) ? kTileRowsBf16 : kTileRowsF32;
   MDZ_REQUIRE(m->ffn % R == 0 && m->d % R == 0, MDZ_ESHAPE, "d %d and ffn %d must be multiples of the tile height %d",
               m->d, m->ffn, R);
-  MDZ_REQUIRE(m->dtype != MDZ_BF16 || (m->d % kKStepBf16 == 0 && m->ffn % kKStepBf16 == 0), MDZ_ESHAPE,
-              "bf16: d and ffn must be multiples of %d", kKStepBf16);
+  MDZ_REQUIRE(!is_16bit(m->dtype) || (m->d % kKStepBf16 == 0 && m->ffn % kKStepBf16 == 0), MDZ_ESHAPE,
+              "bf16 / fp16: d and ffn must be multiples of %d", kKStepBf16);
   MDZ_REQUIRE(m->rms_eps >= 0.f && m->rope_base > 1.f, MDZ_EINVAL, "bad rms_eps / rope_base");
   return MDZ_OK;
 }
 
 static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int max_prefix) {
   MDZ_REQUIRE(kv != nullptr && kv->k != nullptr && kv->v != nullptr, MDZ_EINVAL, "kv descriptor or its buffers NULL");
-  MDZ_REQUIRE(kv->dtype == MDZ_BF16 || kv->dtype == MDZ_FP32, MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
+  MDZ_REQUIRE(dtype_ok(kv->dtype), MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
   MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
               "kv sizes must be positive");
   if (m) {
@@ -200,7 +200,7 @@ static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int m
 // group: query heads per key/value head (1 where only the cache itself is touched)
 static KvGeom geom(const mdz_kv_desc* kv, int group = 1) {
   return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap,
-                (kv->dtype == MDZ_BF16 && kv->head_dim % 32 == 0) ? 1 : 0, group};
+                (is_16bit(kv->dtype) && kv->head_dim % 32 == 0) ? 1 : 0, group};
 }
 
 // One decoder layer over rows = B*T rows of x.  On entry ws.xn holds RMSNorm(x; g_attn of this layer).  The
@@ -278,8 +278,8 @@ int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_
 }
 
 int medusa_pack_tile_rows(int dtype) {
-  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
-  return dtype == MDZ_BF16 ? kTileRowsBf16 : kTileRowsF32;
+  MDZ_REQUIRE(dtype_ok(dtype), MDZ_EINVAL, "bad dtype %d", dtype);
+  return is_16bit(dtype) ? kTileRowsBf16 : kTileRowsF32;
 }
 
 int medusa_gemm_plan(int dtype, int M, int N, int K, int max_split, int32_t* grid, int32_t* band_cols, int32_t* n_stages,
@@ -304,15 +304,15 @@ int medusa_gemm_slot_count(int dtype, int M, int N, int K, int max_split, int co
 }
 
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k) {
-  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
+  MDZ_REQUIRE(dtype_ok(dtype), MDZ_EINVAL, "bad dtype %d", dtype);
   MDZ_REQUIRE(n_rows > 0 && k > 0, MDZ_EINVAL, "packed_bytes: sizes must be positive");
-  if (dtype == MDZ_BF16) return Packed<bf16_t>::padded_rows(n_rows) * Packed<bf16_t>::padded_k(k) * 2;
+  if (is_16bit(dtype)) return Packed<bf16_t>::padded_rows(n_rows) * Packed<bf16_t>::padded_k(k) * 2;
   return round_up(n_rows, kTileRowsF32) * k * 4;
 }
 
 int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, void* stream) {
-  MDZ_REQUIRE(dtype == MDZ_BF16 || dtype == MDZ_FP32, MDZ_EINVAL, "bad dtype %d", dtype);
+  MDZ_REQUIRE(dtype_ok(dtype), MDZ_EINVAL, "bad dtype %d", dtype);
   MDZ_REQUIRE(src && dst, MDZ_EINVAL, "pack: NULL pointer");
   MDZ_REQUIRE(n_rows > 0 && k > 0 && dst_rows >= n_rows, MDZ_EINVAL, "pack: bad sizes");
   return launch_pack_weight(dtype, src, n_rows, k, dst, dst_rows, tile_offset, tile_stride, (hipStream_t)stream);
@@ -320,7 +320,7 @@ int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
 
 int64_t medusa_kv_bytes(const mdz_kv_desc* kv) {
   MDZ_REQUIRE(kv != nullptr, MDZ_EINVAL, "kv descriptor NULL");
-  MDZ_REQUIRE(kv->dtype == MDZ_BF16 || kv->dtype == MDZ_FP32, MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
+  MDZ_REQUIRE(dtype_ok(kv->dtype), MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
   MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
               "kv sizes must be positive");
   return kv_elems(geom(kv)) * elem_bytes(kv->dtype);

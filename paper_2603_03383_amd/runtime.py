@@ -14,7 +14,7 @@ from . import binding as B
 
 
 def torch_dtype(dtype: int):
-    return torch.bfloat16 if dtype == B.MDZ_BF16 else torch.float32
+    return {B.MDZ_BF16: torch.bfloat16, B.MDZ_FP16: torch.float16, B.MDZ_FP32: torch.float32}[dtype]
 
 
 class DeviceModel:

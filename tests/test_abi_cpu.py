@@ -68,3 +68,7 @@ def test_argument_errors_are_status_codes():
     assert b"NULL" in lib.medusa_last_error()
     assert P.medusa_packed_bytes(P.MDZ_BF16, 4096, 4096) == 4096 * 4096 * 2
     assert P.medusa_pack_tile_rows(P.MDZ_BF16) == 32 and P.medusa_pack_tile_rows(P.MDZ_FP32) == 16
+    # fp16 shares the 16-bit layouts
+    assert P.medusa_pack_tile_rows(P.MDZ_FP16) == 32 and P.medusa_packed_bytes(P.MDZ_FP16, 4096, 4096) == 4096 * 4096 * 2
+    with pytest.raises(P.MedusaError):
+        P.medusa_pack_tile_rows(3)

@@ -71,9 +71,12 @@ def test_7b_width_autoregressive_layer_grouped_heads(S_list, max_prefix):
 
 
 def test_two_layer_step_grouped_heads_bf16():
-    w = W.CONFIGS["cfg3_step_1k"].with_(name="step_gqa", n_layers=2, n_kv_heads=8)
+    two_layer_step_case(W.CONFIGS["cfg3_step_1k"].with_(name="step_gqa", n_layers=2, n_kv_heads=8))
+
+
+def two_layer_step_case(w):
     S = w.prefix[0]
-    tol = TOL["bf16"]
+    tol = TOL[w.dtype]
     tree = U.oracle_tree(w)
     T = tree["T"]
     model = U.oracle_model(w, device=G.DEV, heads=False)
@@ -90,7 +93,7 @@ def test_two_layer_step_grouped_heads_bf16():
     g = buf.logits[0].cpu().numpy()
     lscale = _scale(ref["logits"])
     err = np.abs(g - ref["logits"]).max()
-    print(f"GQA step, 2 layers: logits err/scale {err / lscale:.3e}")
+    print(f"{w.name} ({w.dtype}), 2 layers: logits err/scale {err / lscale:.3e}")
     assert err <= tol * lscale
     gpu_am = buf.node_argmax[0].cpu().numpy()
     check_argmax_near_tie(gpu_am, g, ref["logits"], tol * lscale)
@@ -98,13 +101,14 @@ def test_two_layer_step_grouped_heads_bf16():
     assert int(buf.accept_len[0]) == acc["accept_len"] and int(seq_len[0]) == S + acc["accept_len"]
 
 
-def test_paper_shape_one_layer_step_with_heads_vocab_153600():
-    """The paper's shape (Table 1: grouped heads, vocabulary ~153k) at one layer: the selection kernels run with more
-    column chunks than at 128000, the LM-head GEMMs with 4800 tiles."""
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_paper_shape_one_layer_step_with_heads_vocab_153600(dtype):
+    """The paper's shape (Table 1: grouped heads, vocabulary ~153k; five heads; fp16 as in Section 4.1, and bf16) at
+    one layer: the selection kernels run with more column chunks than at 128000, the LM-head GEMMs with 4800 tiles."""
     from tests.test_gpu_parity import check_topk_near_tie
-    w = W.CONFIGS["next3_paper_shape_1k"].with_(n_layers=1, prefix=(200,))
+    w = W.CONFIGS["next3_paper_shape_1k"].with_(n_layers=1, prefix=(200,), dtype=dtype)
     S = w.prefix[0]
-    tol = TOL["bf16"]
+    tol = TOL[dtype]
     tree = U.oracle_tree(w)
     T, K = tree["T"], tree["K"]
     model = U.oracle_model(w, device=G.DEV)
@@ -134,3 +138,5 @@ def test_paper_shape_one_layer_step_with_heads_vocab_153600():
     lscale = _scale(ref["logits"])
     assert np.abs(g - ref["logits"]).max() <= tol * lscale
     check_argmax_near_tie(buf.node_argmax[0].cpu().numpy(), g, ref["logits"], tol * lscale)
+    print(f"paper shape, one layer, {dtype}: head logits err/scale {np.abs(hl - heads['head_logits']).max() / hscale:.3e}, "
+          f"logits err/scale {np.abs(g - ref['logits']).max() / lscale:.3e}")

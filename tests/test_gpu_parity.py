@@ -17,7 +17,10 @@ from tests import util as U
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-5, "bf16": 2e-2}
+# bf16 and fp32: the stated bounds.  fp16 (the paper's own precision, Section 4.1) has no stated bound: it carries 3 more
+# significant bits than bf16 through the same roundings (activations between kernels, K/V in the cache, softmax
+# probabilities), so its bound is the bf16 one scaled by 2^-3.
+TOL = {"fp32": 1e-5, "bf16": 2e-2, "fp16": 2e-2 / 8}
 
 
 def _scale(a):
@@ -331,7 +334,7 @@ def test_accept_fuzz_bit_exact(spec, tid, vocab):
         assert out["next_root"][b] == a["next_root"] and out["last_node"][b] == a["last_node"]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "fp16"])
 def test_kv_compact_bit_exact_ragged_batch(dtype):
     from oracle import tree as OT
     spec = W.TREE64
@@ -483,10 +486,13 @@ def test_cfg4_long_prefix_full_size_layer(S):
 
 def test_cfg5_ragged_batch_16_sequences():
     """16 sequences with seeded ragged prefixes (256..4096), one 7B-shaped layer + LM head + heads + accept +
-    per-sequence compaction.  rows = 1024 > 64, so the GEMMs take the portable kernels."""
-    w = W.CONFIGS["cfg5_ragged_b16"].with_(n_layers=1)
+    per-sequence compaction.  rows = 1024 > 64, so the GEMMs take the many-row kernel."""
+    ragged_batch_case(W.CONFIGS["cfg5_ragged_b16"].with_(n_layers=1))
+
+
+def ragged_batch_case(w):
     Bn = w.batch
-    tol = TOL["bf16"]
+    tol = TOL[w.dtype]
     tree = U.oracle_tree(w)
     T, K = tree["T"], tree["K"]
     max_prefix = max(w.prefix)
