@@ -40,6 +40,8 @@ from __future__ import annotations
 
 import numpy as np
 
+from . import kv8
+
 F64 = np.float64
 
 
@@ -113,7 +115,8 @@ def _layer(x, lw, kc, vc, slots, pos, visible, cfg):
     x [n,d]; kc,vc [Hkv,cap,hd] (this layer's cache, written in place at ``slots``);
     pos [n] RoPE positions; visible [n, n_slots] which cache slots each row attends.
     cfg["n_kv_heads"] (default n_heads) key/value heads: wk, wv are [Hkv*hd, d] (Table 1 of the paper: 32 query
-    heads, 8 key/value heads)."""
+    heads, 8 key/value heads).  cfg["kv_quant"] == "fp8e4m3": the rows are written as 8-bit codes with a scale per
+    row (the KV compression the paper's Section 4.2 / 5 point to) and read back dequantised."""
     H, hd = cfg["n_heads"], cfg["head_dim"]
     Hkv = cfg.get("n_kv_heads") or H
     assert H % Hkv == 0
@@ -125,8 +128,12 @@ def _layer(x, lw, kc, vc, slots, pos, visible, cfg):
     q = rope(q.reshape(n, H, hd).transpose(1, 0, 2), pos, cfg["rope_base"])      # [H,n,hd]
     k = rope(k.reshape(n, Hkv, hd).transpose(1, 0, 2), pos, cfg["rope_base"])        # [Hkv,n,hd]
     v = v.reshape(n, Hkv, hd).transpose(1, 0, 2)
-    kc[:, slots, :] = round_to_storage(k, cfg["dtype"])
-    vc[:, slots, :] = round_to_storage(v, cfg["dtype"])
+    if cfg.get("kv_quant") == "fp8e4m3":        # 8-bit cache rows (oracle/kv8.py states the format)
+        kc[:, slots, :] = kv8.roundtrip_rows(k)
+        vc[:, slots, :] = kv8.roundtrip_rows(v)
+    else:
+        kc[:, slots, :] = round_to_storage(k, cfg["dtype"])
+        vc[:, slots, :] = round_to_storage(v, cfg["dtype"])
     att = _attend(q, kc, vc, visible, hd)                                          # [H,n,hd]
     att = att.transpose(1, 0, 2).reshape(n, H * hd)
     x = x + att @ np.asarray(lw["wo"], dtype=F64).T
