@@ -39,7 +39,8 @@ def algorithmic_bytes(w, with_heads: bool):
     gemm_layers = w.n_layers * layer_w
     lm = w.vocab * w.d * es
     heads = K * (w.d * w.d + w.vocab * w.d) * es if with_heads else 0
-    kv_row = 2 * kvd * es                                         # K and V of one slot, one layer
+    # K and V of one slot, one layer; 8-bit rows: one byte per feature plus one fp32 scale per head and matrix
+    kv_row = 2 * (kvd + 4 * w.kv_heads) if w.kv_quant else 2 * kvd * es
     kv_prefix = sum(w.prefix) * kv_row * w.n_layers
     kv_tree = 2 * w.batch * T * kv_row * w.n_layers               # written + read
     embed = w.batch * T * w.d * es
@@ -69,7 +70,7 @@ def build_device(w, with_heads):
             dm.add_medusa_head(W.medusa_w1(w, k, dev), None, W.medusa_lm(w, k, dev))
     dm.finalize()
     max_prefix = max(w.prefix) + (w.n_medusa + 1)
-    kv = P.DeviceKV(dm, batch=w.batch, cap=max_prefix + w.tree.n_nodes)
+    kv = P.DeviceKV(dm, batch=w.batch, cap=max_prefix + w.tree.n_nodes, quant=w.kv_quant)
     for b in range(w.batch):
         for l in range(w.n_layers):
             k, v = W.prefix_kv(w, l, b, dev)
@@ -96,7 +97,7 @@ def cpu_baseline(w, with_heads, budget_s=20.0):
     tree = OT.build_tree(w.tree.caps, w.tree.budgets)
     T = tree["T"]
     cfg = dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, n_kv_heads=w.kv_heads, head_dim=w.head_dim, ffn=w.ffn,
-               vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype)
+               vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=w.dtype, kv_quant=w.kv_quant)
     gen = "cuda:0"
     S = w.prefix[0]
     x = f32(W.hidden_state(w, "bench_x", T, gen)).astype(np.float64)
@@ -149,6 +150,7 @@ def main():
     ap.add_argument("--workload", default="cfg3_step_1k")
     ap.add_argument("--no-heads", action="store_true", help="time verify+accept+compact only")
     ap.add_argument("--prefix", type=int, default=None, help="override the workload's prefix length (every sequence)")
+    ap.add_argument("--kv8", action="store_true", help="8-bit KV cache rows (E4M3 codes + one fp32 scale per row)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -161,6 +163,8 @@ def main():
     import paper_2603_03383_amd as P
 
     w = W.CONFIGS[args.workload]
+    if args.kv8:
+        w = w.with_(name=f"{w.name}+kv8", kv_quant="fp8e4m3")
     if args.prefix is not None:
         w = w.with_(name=f"{w.name}@prefix{args.prefix}", prefix=(args.prefix,) * w.batch)
     with_heads = not args.no_heads and w.n_layers > 1
@@ -239,7 +243,7 @@ def main():
     if not layer_only and with_heads:
         n_chain = 16
         cap_chain = max(w.prefix) + n_chain * (w.n_medusa + 1)
-        kv_c = P.DeviceKV(dm, batch=Bn, cap=cap_chain + T)
+        kv_c = P.DeviceKV(dm, batch=Bn, cap=cap_chain + T, quant=w.kv_quant)
         for b in range(Bn):
             for l in range(w.n_layers):
                 k, v = W.prefix_kv(w, l, b, dm.device)
@@ -284,7 +288,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "tree_nodes": T, "prefix": list(w.prefix), "batch": Bn,
-                   "layers": w.n_layers, "with_medusa_heads": with_heads,
+                   "layers": w.n_layers, "with_medusa_heads": with_heads, "kv_rows": w.kv_quant or w.dtype,
                    "step": "tree_verify_layer" if layer_only else "medusa_heads+tree_verify_step+accept_longest_prefix+kv_compact"},
         "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
                 "frac_of_peak": step_gbps / HBM_PEAK_GBPS,

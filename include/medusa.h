@@ -50,6 +50,14 @@ typedef enum {
 typedef enum { MDZ_TREE_15 = 0, MDZ_TREE_64 = 1, MDZ_TREE_1 = 2, MDZ_TREE_64_K5 = 3 /* 64 nodes, five heads */ } mdz_tree_id;
 typedef enum { MDZ_BF16 = 0, MDZ_FP32 = 1, MDZ_FP16 = 2 /* IEEE binary16: same layouts and kernels as bf16 */ } mdz_dtype;
 
+/* Cache rows as stored.  MDZ_KV_FP8E4M3: the KV compression the paper points to for long sequences (Sections 4.2
+ * and 5; the paper fixes no format): a row (one slot of one key/value head) is head_dim OCP FP8 E4M3 codes plus one
+ * fp32 scale = max|row| / 448 (1 for a zero row); code = the E4M3 value nearest to x / scale, ties to even, decided in
+ * fp32 on the fp32 value of the row (K after RoPE); attention reads value(code) * scale.  Half the bytes per slot
+ * (132 instead of 256 per head and matrix at head_dim 128); `dtype` still names the type of rows at the boundary
+ * (medusa_kv_write quantises, medusa_kv_read returns value(code) * scale rounded to dtype). */
+typedef enum { MDZ_KV_PLAIN = 0, MDZ_KV_FP8E4M3 = 1 } mdz_kv_quant;
+
 #define MDZ_MAX_HEADS 8
 
 /* HOST struct: the decoder's shape. d == n_heads * head_dim (no bias).  n_kv_heads: key/value heads of
@@ -95,13 +103,16 @@ typedef struct {
 
 /* HOST struct: the KV cache.  k and v are two device allocations of medusa_kv_bytes() bytes each whose
  * internal layout belongs to the library (tiled for the attention kernels); fill and inspect them with
- * medusa_kv_write / medusa_kv_read.  cap = slots per sequence; a verify pass with prefix length S
+ * medusa_kv_write / medusa_kv_read.  Zero-fill both once after allocating them: the attention kernels load whole
+ * blocks of 32 slots and multiply the slots beyond a sequence's length by zero, which only finite contents survive.
+ * cap = slots per sequence; a verify pass with prefix length S
  * writes slots S..S+T-1, so S + T <= cap is required. */
 typedef struct {
   void* k;
   void* v;
   int32_t n_layers, batch, n_heads, head_dim, cap; /* n_heads: key/value heads (the heads the cache holds) */
   int32_t dtype; /* mdz_dtype */
+  int32_t quant; /* mdz_kv_quant; MDZ_KV_FP8E4M3 needs a 16-bit dtype, head_dim 128 and a tree of 64 nodes or 1 node */
 } mdz_kv_desc;
 
 /* ---- introspection (all HOST out-pointers) ------------------------------------------------- */

@@ -21,6 +21,8 @@ MDZ_BF16, MDZ_FP32, MDZ_FP16 = 0, 1, 2
 MDZ_TREE_15, MDZ_TREE_64, MDZ_TREE_1, MDZ_TREE_64_K5 = 0, 1, 2, 3
 MDZ_MAX_HEADS = 8
 DTYPES = {"bf16": MDZ_BF16, "fp32": MDZ_FP32, "fp16": MDZ_FP16}
+MDZ_KV_PLAIN, MDZ_KV_FP8E4M3 = 0, 1
+KV_QUANT = {"": MDZ_KV_PLAIN, "fp8e4m3": MDZ_KV_FP8E4M3}
 TREES = {"tree15": MDZ_TREE_15, "tree64": MDZ_TREE_64, "tree1": MDZ_TREE_1, "tree64k5": MDZ_TREE_64_K5}
 
 
@@ -49,7 +51,7 @@ class Weights(C.Structure):
 
 class KvDesc(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("n_layers", C.c_int32), ("batch", C.c_int32),
-                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32)]
+                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32), ("quant", C.c_int32)]
 
 
 _lib = None

@@ -8,6 +8,9 @@
 // halves of every 16-feature step, so a score is a 64-term sum per lane plus one exchange with lane ^ 32.  In a V
 // unit lane l holds feature 32t + l % 32 for 8 keys; their probabilities come from the lanes that own those keys.
 // Waves merge through LDS, key-splits through a second small kernel, both in a fixed order.
+// Q8 = true: 8-bit rows (common.h): a block is 4 K units + 4 V units + 2 x 32 scales; a lane's 16 bytes of K unit j are
+// its 8 features of k-steps 2j and 2j+1, its 16 bytes of V unit t the 8 keys of s2 = 0 and of s2 = 1; the score of key
+// k is multiplied by the key's K scale and its probability by the key's V scale, in fp32.
 #include "kernels.h"
 
 namespace mdz {
@@ -28,6 +31,12 @@ __device__ inline float half_sum(float v) {
   for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+__device__ inline void unpack8_fp8(u32x4 v, int half, float (&f)[8]) {  // the 8 codes in words 2*half, 2*half+1
+  const uint32_t w0 = half ? v.z : v.x, w1 = half ? v.w : v.y;
+  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(w0, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(w0, true);
+  const auto c = __builtin_amdgcn_cvt_pk_f32_fp8(w1, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(w1, true);
+  f[0] = a[0], f[1] = a[1], f[2] = b[0], f[3] = b[1], f[4] = c[0], f[5] = c[1], f[6] = d[0], f[7] = d[1];
+}
 template <typename E>
 __device__ inline void unpack8(u32x4 v, float (&f)[8]) {
   f[0] = Elem16<E>::lo(v.x), f[1] = Elem16<E>::hi(v.x);
@@ -37,7 +46,7 @@ __device__ inline void unpack8(u32x4 v, float (&f)[8]) {
 }
 }  // namespace
 
-template <typename E>
+template <typename E, bool Q8>
 __global__ void __launch_bounds__(256)
     attn_decode_kernel(const E* __restrict__ q, KvGeom g, const E* __restrict__ kc, const E* __restrict__ vc,
                        int layer, const int32_t* __restrict__ seq_len, int max_prefix, E* __restrict__ att_out,
@@ -64,27 +73,49 @@ __global__ void __launch_bounds__(256)
     for (int e = 0; e < 8; ++e) qf[ks][e] *= scale_log2;
   }
 
-  const int64_t head_base = kv_head_base(g, layer, b, h / g.group);  // query head h reads key/value head h / group
-  const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
-  const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+  // query head h reads key/value head h / group.  16-bit rows: unit i of block blk at kp[blk*512 + i*64]; 8-bit
+  // rows: at kp[blk*264 + i*64], the scale of key `key` at ksc[blk*1056 + key]
+  constexpr int kBlkPieces = Q8 ? kKv8BlockBytes / 16 : 512;
+  const u32x4* kp;
+  const u32x4* vp;
+  const float* ksc = nullptr;
+  const float* vsc = nullptr;
+  if constexpr (Q8) {
+    const int64_t hb = kv8_head_base(g, layer, b, h / g.group);
+    const uint8_t* k0 = reinterpret_cast<const uint8_t*>(kc) + hb;
+    const uint8_t* v0 = reinterpret_cast<const uint8_t*>(vc) + hb;
+    kp = reinterpret_cast<const u32x4*>(k0) + lane, vp = reinterpret_cast<const u32x4*>(v0) + lane;
+    ksc = reinterpret_cast<const float*>(k0 + 4096) + key, vsc = reinterpret_cast<const float*>(v0 + 4096) + key;
+  } else {
+    const int64_t head_base = kv_head_base(g, layer, b, h / g.group);
+    kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;
+    vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+  }
 
   float m_run = -INFINITY, l_run = 0.f;
   float o[4] = {0.f, 0.f, 0.f, 0.f};  // feature 32t + key, over the keys this half-wave owns
   for (int blk = blk_begin + wave; blk < blk_end; blk += 4) {
-    u32x4 kd[8], vd[8];
+    constexpr int kUnits = Q8 ? 4 : 8;
+    u32x4 kd[kUnits], vd[kUnits];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) kd[i] = kp[(int64_t)blk * 512 + i * 64];
+    for (int i = 0; i < kUnits; ++i) kd[i] = kp[(int64_t)blk * kBlkPieces + i * 64];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vd[i] = vp[(int64_t)blk * 512 + i * 64];
+    for (int i = 0; i < kUnits; ++i) vd[i] = vp[(int64_t)blk * kBlkPieces + i * 64];
+    float k_scale = 1.f, v_scale = 1.f;
+    if constexpr (Q8) k_scale = ksc[(int64_t)blk * (kKv8BlockBytes / 4)], v_scale = vsc[(int64_t)blk * (kKv8BlockBytes / 4)];
     float s = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       float kf[8];
-      unpack8<E>(kd[ks], kf);
+      if constexpr (Q8)
+        unpack8_fp8(kd[ks >> 1], ks & 1, kf);
+      else
+        unpack8<E>(kd[ks], kf);
 #pragma unroll
       for (int e = 0; e < 8; ++e) s += qf[ks][e] * kf[e];
     }
     s += __shfl_xor(s, 32, 64);  // both half-waves now hold the score of key `key`
+    s *= k_scale;
     s = (blk * 32 + key < n_slots) ? s : -INFINITY;
     const float m_new = fmaxf(m_run, half_max(s));  // finite: a block in range holds at least one visible slot
     const float p = fast_exp2_attn(s - m_new);
@@ -94,15 +125,19 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
     for (int t = 0; t < 4; ++t) o[t] *= alpha;
     // V unit (2t + s2): feature 32t + key, keys 16*s2 + 8*(e/4) + 4*half + e%4; the probability of key k lives in lane k
+    const float pv = Q8 ? (blk * 32 + key < n_slots ? p * v_scale : 0.f) : p;  // the key's V scale rides on its probability
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       float pe[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pe[e] = __shfl(p, 16 * s2 + 8 * (e >> 2) + 4 * half + (e & 3), 64);
+      for (int e = 0; e < 8; ++e) pe[e] = __shfl(pv, 16 * s2 + 8 * (e >> 2) + 4 * half + (e & 3), 64);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         float vf[8];
-        unpack8<E>(vd[2 * t + s2], vf);
+        if constexpr (Q8)
+          unpack8_fp8(vd[t], s2, vf);
+        else
+          unpack8<E>(vd[2 * t + s2], vf);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[t] += pe[e] * vf[e];
       }
@@ -175,7 +210,7 @@ int64_t attn_decode_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kHD + 2) * 4;
 }
 
-template <typename E>
+template <typename E, bool Q8>
 static int launch_attention_decode_t(const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
                                      const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                                      int64_t scratch_bytes, hipStream_t st) {
@@ -187,7 +222,7 @@ static int launch_attention_decode_t(const void* q, const KvGeom& g, const void*
               "decode attention: scratch too small");
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (int64_t)B * nq * splits * kHD;
-  attn_decode_kernel<E><<<dim3(splits, nq, B), 256, 0, st>>>((const E*)q, g, (const E*)kc, (const E*)vc, layer, seq_len,
+  attn_decode_kernel<E, Q8><<<dim3(splits, nq, B), 256, 0, st>>>((const E*)q, g, (const E*)kc, (const E*)vc, layer, seq_len,
                                                              max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
@@ -200,8 +235,11 @@ static int launch_attention_decode_t(const void* q, const KvGeom& g, const void*
 int launch_attention_decode(int dtype, const void* q, const KvGeom& g, const void* kc, const void* vc, int layer,
                             const int32_t* seq_len, int B, int max_prefix, void* att_out, void* scratch,
                             int64_t scratch_bytes, hipStream_t st) {
-  MDZ_WITH_ELEM16(dtype, return launch_attention_decode_t<E>(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
-                                                             scratch_bytes, st));
+  if (g.quant)
+    MDZ_WITH_ELEM16(dtype, return (launch_attention_decode_t<E, true>(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out,
+                                                                      scratch, scratch_bytes, st)));
+  MDZ_WITH_ELEM16(dtype, return (launch_attention_decode_t<E, false>(q, g, kc, vc, layer, seq_len, B, max_prefix, att_out,
+                                                                     scratch, scratch_bytes, st)));
 }
 
 }  // namespace mdz

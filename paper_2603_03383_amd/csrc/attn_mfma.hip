@@ -11,6 +11,9 @@
 // The tree mask is one 64-bit word per query (a compile-time table) tested only in blocks that reach
 // past the prefix.  Waves merge through LDS, key-splits through a small second kernel, both in a fixed
 // order, so results are deterministic.
+// Q8 = true: the cache holds 8-bit rows (E4M3 codes + one fp32 scale per row, common.h).  A block is then 4 K units,
+// 4 V units and 2 x 32 scales; codes convert exactly to the 16-bit element type in registers (two k-steps per 16-byte
+// load), the K scales multiply the scores and the V scales the probabilities, both in fp32, so the MFMAs are the same.
 // Key-splits: when the kernel starts from the QKV partial sums, the last split owns every block that holds a
 // tree slot (it is the one that has to produce those K / V rows first) and the other splits share the blocks
 // that hold prefix keys only, which need nothing but Q: the long dependent chain (reduce K and V, write them,
@@ -29,6 +32,14 @@ constexpr int kQRow = kHD * 2 + 16;  // bytes per staged Q row
 constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 8 E4M3 codes (words 2*half, 2*half+1 of v) -> 8 elements
+template <typename E>
+__device__ inline u32x4 fp8x8_to_elem(u32x4 v, int half) {
+  const uint32_t w0 = half ? v.z : v.x, w1 = half ? v.w : v.y;
+  return u32x4{Elem16<E>::from_fp8x2(w0, false), Elem16<E>::from_fp8x2(w0, true), Elem16<E>::from_fp8x2(w1, false),
+               Elem16<E>::from_fp8x2(w1, true)};
+}
 
 template <typename E>
 __device__ inline u32x4 pack8(const float* v) {
@@ -92,7 +103,7 @@ __device__ inline void rope16(const float* cs_row, int seg, float (&lo)[16], flo
 // cos/sin table cs [row][64][2]), keeps q in LDS, and — if its key range reaches the tree slots — writes the 64
 // tree rows of K and V of its head into the cache before reading them back like any other key.  Workgroups of
 // the same head that both reach the tree slots write identical values.
-template <typename E>
+template <typename E, bool Q8>
 __global__ void __launch_bounds__(256)
     attn_tree_mfma_kernel(int tree, const E* __restrict__ q, const Partials qkv, const float* __restrict__ cs,
                           KvGeom g, E* __restrict__ kc, E* __restrict__ vc, int layer,
@@ -149,15 +160,54 @@ __global__ void __launch_bounds__(256)
       stage_q(lo[0], hi[0]);
       const int slot = S + row;
       rope16(cs_row, seg, lo[1], hi[1]);
-      // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack8<E>(lo[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack8<E>(lo[1] + 8);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack8<E>(hi[1]);
-      *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack8<E>(hi[1] + 8);
+      if constexpr (Q8) {
+        // row scales: the largest magnitude over the 4 threads (seg) of the row, then codes of this thread's 2 x 16 features
+        float am[2] = {0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = from_float<E>(lo[2][i]);
-        vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = from_float<E>(hi[2][i]);
+        for (int m = 0; m < 2; ++m) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) am[m] = fmaxf(am[m], fmaxf(fabsf(lo[1 + m][i]), fabsf(hi[1 + m][i])));
+          am[m] = fmaxf(am[m], __shfl_xor(am[m], 1, 64));
+          am[m] = fmaxf(am[m], __shfl_xor(am[m], 2, 64));
+        }
+        const float ks = kv8_scale_of(am[0]), vs = kv8_scale_of(am[1]);
+        uint8_t* k8 = reinterpret_cast<uint8_t*>(kc) + kv8_head_base(g, layer, b, hk);
+        uint8_t* v8 = reinterpret_cast<uint8_t*>(vc) + kv8_head_base(g, layer, b, hk);
+        // 8 consecutive features of one key are 8 contiguous bytes of the 8-bit K layout
+#pragma unroll
+        for (int gh2 = 0; gh2 < 2; ++gh2) {
+          const float* a = lo[1] + 8 * gh2;
+          const float* c = hi[1] + 8 * gh2;
+          *reinterpret_cast<uint2*>(k8 + kv8_k_code(slot, 16 * seg + 8 * gh2)) =
+              uint2{kv8_pack4(a[0], a[1], a[2], a[3], ks), kv8_pack4(a[4], a[5], a[6], a[7], ks)};
+          *reinterpret_cast<uint2*>(k8 + kv8_k_code(slot, 64 + 16 * seg + 8 * gh2)) =
+              uint2{kv8_pack4(c[0], c[1], c[2], c[3], ks), kv8_pack4(c[4], c[5], c[6], c[7], ks)};
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i += 4) {
+          const uint32_t wl = kv8_pack4(lo[2][i], lo[2][i + 1], lo[2][i + 2], lo[2][i + 3], vs);
+          const uint32_t wh = kv8_pack4(hi[2][i], hi[2][i + 1], hi[2][i + 2], hi[2][i + 3], vs);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v8[kv8_v_code(slot, 16 * seg + i + e)] = (uint8_t)(wl >> (8 * e));
+            v8[kv8_v_code(slot, 64 + 16 * seg + i + e)] = (uint8_t)(wh >> (8 * e));
+          }
+        }
+        if (seg == 0) {
+          *reinterpret_cast<float*>(k8 + kv8_scale(slot)) = ks;
+          *reinterpret_cast<float*>(v8 + kv8_scale(slot)) = vs;
+        }
+      } else {
+        // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack8<E>(lo[1]);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack8<E>(lo[1] + 8);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack8<E>(hi[1]);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack8<E>(hi[1] + 8);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = from_float<E>(lo[2][i]);
+          vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = from_float<E>(hi[2][i]);
+        }
       }
     } else {
       float lo[1][16], hi[1][16];
@@ -172,9 +222,24 @@ __global__ void __launch_bounds__(256)
   const uint64_t mq[2] = {t.anc_mask[qi], t.anc_mask[32 + qi]};
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
 
-  const int64_t head_base = kv_head_base(g, layer, b, hk);
-  const u32x4* kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;  // + blk*512 + unit*64
-  const u32x4* vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+  // 16-bit rows: block blk, unit i at kp[blk*512 + i*64].  8-bit rows: a block is 264 16-byte pieces: unit i at
+  // kp[blk*264 + i*64], the four scales of keys 8j + 4gh .. +3 at ks_p[blk*264 + 2j]
+  constexpr int kBlkPieces = Q8 ? kKv8BlockBytes / 16 : 512;
+  const u32x4* kp;
+  const u32x4* vp;
+  const u32x4* ks_p = nullptr;
+  const u32x4* vs_p = nullptr;
+  if constexpr (Q8) {
+    const int64_t hb = kv8_head_base(g, layer, b, hk);
+    const u32x4* k0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(kc) + hb);
+    const u32x4* v0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(vc) + hb);
+    kp = k0 + lane, vp = v0 + lane;
+    ks_p = k0 + 256 + gh, vs_p = v0 + 256 + gh;
+  } else {
+    const int64_t head_base = kv_head_base(g, layer, b, hk);
+    kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;
+    vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+  }
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
   f32x16 o[4][2];
@@ -188,9 +253,10 @@ __global__ void __launch_bounds__(256)
   // K is double buffered one block ahead; V of a block is requested when its scores start, so its
   // latency hides behind the 16 score MFMAs and the softmax arithmetic (and the other waves of the CU).
   u32x4 kb[2][8];
-  auto load_k = [&](int blk, u32x4 (&kd)[8]) {
+  auto load_k = [&](int blk, u32x4 (&kd)[8]) {  // 8-bit rows: kd[0..3] codes, kd[4..7] the lane's 16 scales
 #pragma unroll
-    for (int i = 0; i < 8; ++i) kd[i] = kp[(int64_t)blk * 512 + i * 64];
+    for (int i = 0; i < 8; ++i)
+      kd[i] = (Q8 && i >= 4) ? ks_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : kp[(int64_t)blk * kBlkPieces + i * 64];
   };
   auto process = [&](int blk, const u32x4 (&kd)[8]) {
     // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
@@ -198,7 +264,8 @@ __global__ void __launch_bounds__(256)
     asm volatile("" ::: "memory");
     u32x4 vd[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vd[i] = vp[(int64_t)blk * 512 + i * 64];
+    for (int i = 0; i < 8; ++i)
+      vd[i] = (Q8 && i >= 4) ? vs_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : vp[(int64_t)blk * kBlkPieces + i * 64];
     f32x16 sc[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
@@ -206,10 +273,11 @@ __global__ void __launch_bounds__(256)
       for (int r = 0; r < 16; ++r) sc[u][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
+      const u32x4 ka = Q8 ? fp8x8_to_elem<E>(kd[ks >> 1], ks & 1) : kd[ks];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const u32x4 qv = *reinterpret_cast<const u32x4*>(qfrag + u * 32 * kQRow + ks * 32);
-        sc[u] = Elem16<E>::mfma(kd[ks], qv, sc[u]);
+        sc[u] = Elem16<E>::mfma(ka, qv, sc[u]);
       }
     }
     // Visibility of this block's 32 keys for the lane's query, as one 32-bit word: prefix keys are
@@ -230,7 +298,8 @@ __global__ void __launch_bounds__(256)
       float bmax = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float s = sc[u][r] * scale_log2;
+        // register r is key 8*(r/4) + 4*gh + r%4 of the block; its scale is component r%4 of scale piece r/4
+        float s = sc[u][r] * (Q8 ? __uint_as_float(kd[4 + (r >> 2)][r & 3]) * scale_log2 : scale_log2);
         s = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s : -INFINITY;
         sc[u][r] = s;
         bmax = fmaxf(bmax, s);
@@ -245,6 +314,7 @@ __global__ void __launch_bounds__(256)
       for (int r = 0; r < 16; r += 2) {
         float p0 = fast_exp2(sc[u][r] - m_safe), p1 = fast_exp2(sc[u][r + 1] - m_safe);
         sum += p0 + p1;
+        if constexpr (Q8) p0 *= __uint_as_float(vd[4 + (r >> 2)][r & 3]), p1 *= __uint_as_float(vd[4 + (r >> 2)][(r & 3) + 1]);
         pk[r >> 1] = Elem16<E>::pack2(p0, p1);
       }
       l_run[u] = l_run[u] * alpha[u] + sum;
@@ -264,8 +334,9 @@ __global__ void __launch_bounds__(256)
     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
+        const u32x4 va = Q8 ? fp8x8_to_elem<E>(vd[tt], s2) : vd[tt * 2 + s2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) o[tt][u] = Elem16<E>::mfma(vd[tt * 2 + s2], pf[u][s2], o[tt][u]);
+        for (int u = 0; u < 2; ++u) o[tt][u] = Elem16<E>::mfma(va, pf[u][s2], o[tt][u]);
       }
   };
 
@@ -416,7 +487,7 @@ int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
 }
 
-template <typename E>
+template <typename E, bool Q8>
 static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
                                    void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                                    void* scratch, int64_t scratch_bytes, hipStream_t st) {
@@ -424,7 +495,7 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
   if (B == 0) return MDZ_OK;
   static bool attr_set = false;
   if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E>),
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E, Q8>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
     attr_set = true;
   }
@@ -436,7 +507,7 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
   float* part_ml = part_o + (int64_t)B * nq * splits * kTQ * kHD;
   dim3 grid(splits, nq, B);
   const Partials none = single_slot(nullptr, 0, 0);
-  attn_tree_mfma_kernel<E><<<grid, 256, kAttnLdsBytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
+  attn_tree_mfma_kernel<E, Q8><<<grid, 256, kAttnLdsBytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
                                                              layer, seq_len, max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
@@ -449,8 +520,11 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
 int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g,
                           void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                           void* scratch, int64_t scratch_bytes, hipStream_t st) {
-  MDZ_WITH_ELEM16(dtype, return launch_attention_mfma_t<E>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
-                                                           att_out, scratch, scratch_bytes, st));
+  if (g.quant)
+    MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, true>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
+                                                                    att_out, scratch, scratch_bytes, st)));
+  MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, false>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
+                                                                   att_out, scratch, scratch_bytes, st)));
 }
 
 }  // namespace mdz

@@ -96,6 +96,11 @@ struct Elem16<bf16_t> {
   }
   __device__ static inline float lo(uint32_t w) { return __uint_as_float(w << 16); }
   __device__ static inline float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+  __device__ static inline uint32_t from_fp8x2(uint32_t src, bool hi_word) {  // two E4M3 codes -> two elements (exact)
+    typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+    return hi_word ? __builtin_bit_cast(uint32_t, (v2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(src, 1.0f, true))
+                   : __builtin_bit_cast(uint32_t, (v2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(src, 1.0f, false));
+  }
   __device__ static inline f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
     typedef __bf16 v8 __attribute__((ext_vector_type(8)));
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
@@ -109,6 +114,10 @@ struct Elem16<f16_t> {
   }
   __device__ static inline float lo(uint32_t w) { return (float)__builtin_bit_cast(h2, w).x; }
   __device__ static inline float hi(uint32_t w) { return (float)__builtin_bit_cast(h2, w).y; }
+  __device__ static inline uint32_t from_fp8x2(uint32_t src, bool hi_word) {
+    return hi_word ? __builtin_bit_cast(uint32_t, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(src, 1.0f, true))
+                   : __builtin_bit_cast(uint32_t, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(src, 1.0f, false));
+  }
   __device__ static inline f32x16_t mfma(u32x4_t a, u32x4_t b, f32x16_t c) {
     typedef _Float16 v8 __attribute__((ext_vector_type(8)));
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
@@ -198,6 +207,7 @@ struct KvGeom {
   int n_layers, batch, n_heads, head_dim, cap;  // n_heads: key/value heads (the heads the cache holds)
   int tiled;  // 1: bf16 block layout above (head_dim % 32 == 0); 0: plain
   int group;  // query heads per key/value head (grouped-query attention; 1: plain multi-head attention)
+  int quant;  // 1: 8-bit rows (E4M3 codes + one fp32 scale per row, layout below); needs tiled and head_dim 128
 };
 __host__ __device__ inline int q_heads(const KvGeom& g) { return g.n_heads * g.group; }
 __host__ __device__ inline int kv_cap_pad(const KvGeom& g) { return g.tiled ? (g.cap + 31) & ~31 : g.cap; }
@@ -222,6 +232,48 @@ __host__ __device__ inline int64_t v_index(const KvGeom& g, int l, int b, int h,
 inline int64_t kv_elems(const KvGeom& g) {
   return (int64_t)g.n_layers * g.batch * g.n_heads * kv_cap_pad(g) * g.head_dim;
 }
+
+// ---- 8-bit KV cache layout (MDZ_KV_FP8E4M3, head_dim 128) -----------------------------------------
+// The KV compression the paper points to for long sequences (Sections 4.2 and 5).  A row (one slot of one
+// key/value head) is 128 OCP FP8 E4M3 codes and one fp32 scale: scale = max|row| / 448 (1 for a zero row),
+// code = nearest E4M3 value of x / scale (ties to even, decided in fp32), value read back = value(code) * scale.
+// Per (layer, seq, head) the slots are grouped in blocks of 32; a block is 4 units of 1 KiB (64 lanes x 16 B)
+// followed by the 32 scales, 4224 B in all, so a wave streams a block as one contiguous piece:
+//   K unit j: lane l holds key (l % 32) and the 16 features 32j + 16p + 8(l / 32) + e, byte 8p + e (p < 2, e < 8):
+//     the 8 bytes of one p convert to the A operand of k-step 2j + p of the 16-bit layout above.
+//   V unit t: lane l holds feature 32t + (l % 32) and 16 keys, byte 8 s2 + e for key 16 s2 + 8(e / 4) + 4(l / 32) + e % 4:
+//     the 8 bytes of one s2 convert to the A operand of unit (2t + s2) of the 16-bit layout.
+constexpr int kKv8BlockBytes = 32 * 128 + 32 * 4;
+constexpr float kE4M3Max = 448.0f;
+__host__ __device__ inline int64_t kv8_head_base(const KvGeom& g, int l, int b, int h) {  // bytes
+  return (((int64_t)l * g.batch + b) * g.n_heads + h) * (int64_t)(kv_cap_pad(g) >> 5) * kKv8BlockBytes;
+}
+__host__ __device__ inline int64_t kv8_k_code(int pos, int i) {  // byte offset inside the head's region
+  const int blk = pos >> 5, key = pos & 31, j = i >> 5, p = (i >> 4) & 1, gh = (i >> 3) & 1, e = i & 7;
+  return (int64_t)blk * kKv8BlockBytes + j * 1024 + (key + 32 * gh) * 16 + p * 8 + e;
+}
+__host__ __device__ inline int64_t kv8_v_code(int pos, int i) {
+  const int blk = pos >> 5, kk = pos & 31, s2 = kk >> 4, ehi = (kk >> 3) & 1, kh = (kk >> 2) & 1, elo = kk & 3;
+  const int t = i >> 5, row = i & 31;
+  return (int64_t)blk * kKv8BlockBytes + t * 1024 + (row + 32 * kh) * 16 + s2 * 8 + ehi * 4 + elo;
+}
+__host__ __device__ inline int64_t kv8_scale(int pos) {  // byte offset of the slot's scale
+  return (int64_t)(pos >> 5) * kKv8BlockBytes + 4096 + (pos & 31) * 4;
+}
+inline int64_t kv8_bytes(const KvGeom& g) {
+  return (int64_t)g.n_layers * g.batch * g.n_heads * (kv_cap_pad(g) >> 5) * kKv8BlockBytes;
+}
+#if defined(__HIPCC__)
+// quantiser shared by every kernel that writes 8-bit rows: scale of a row from its largest magnitude, and four
+// values -> four codes (IEEE fp32 division, clamp, the hardware's round-to-nearest-even E4M3 conversion)
+__device__ inline float kv8_scale_of(float amax) { return amax > 0.f ? amax / kE4M3Max : 1.0f; }
+__device__ inline uint32_t kv8_pack4(float a, float b, float c, float d, float s) {
+  auto q = [&](float v) { return fminf(fmaxf(v / s, -kE4M3Max), kE4M3Max); };
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(q(a), q(b), 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(q(c), q(d), w, true);
+  return (uint32_t)w;
+}
+#endif
 
 // ---- device copies of the trees -----------------------------------------------------------------
 static __constant__ TreeTables c_trees[kNumTrees] = {kTree15, kTree64, kTree1, kTree64K5};

@@ -192,7 +192,8 @@ template <typename E>
 __device__ inline uint2 pack4(float a, float b, float c, float d) {
   return uint2{Elem16<E>::pack2(a, b), Elem16<E>::pack2(c, d)};
 }
-template <typename E>
+// Q8: the cache holds 8-bit rows (common.h); the 16 threads of a (head, matrix) row agree on the row's scale first.
+template <typename E, bool Q8>
 __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partials part, const float* __restrict__ cs,
                                                                E* __restrict__ q_out, KvGeom g, E* __restrict__ kc,
                                                                E* __restrict__ vc, int layer,
@@ -227,12 +228,46 @@ __global__ void __launch_bounds__(192) rope_kvwrite_vec_kernel(int tree, Partial
     }
   if (which == 2) {
     const float va[4] = {a.x, a.y, a.z, a.w}, vb[4] = {bq.x, bq.y, bq.z, bq.w};
+    if constexpr (Q8) {
+      float am = fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
+                       fmaxf(fmaxf(fabsf(bq.x), fabsf(bq.y)), fmaxf(fabsf(bq.z), fabsf(bq.w))));
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+      const float vs = kv8_scale_of(am);
+      uint8_t* v8 = reinterpret_cast<uint8_t*>(vc) + kv8_head_base(g, layer, b, hk);
+      const uint32_t wl = kv8_pack4(a.x, a.y, a.z, a.w, vs), wh = kv8_pack4(bq.x, bq.y, bq.z, bq.w, vs);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v8[kv8_v_code(slot, i + e)] = (uint8_t)(wl >> (8 * e));
+        v8[kv8_v_code(slot, i + 64 + e)] = (uint8_t)(wh >> (8 * e));
+      }
+      if (w % 16 == 0) *reinterpret_cast<float*>(v8 + kv8_scale(slot)) = vs;
+      return;
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       vc[v_index(g, layer, b, hk, slot, i + e)] = from_float<E>(va[e]);
       vc[v_index(g, layer, b, hk, slot, i + 64 + e)] = from_float<E>(vb[e]);
     }
     return;
+  }
+  if constexpr (Q8) {
+    if (which == 1) {  // rotated key row -> codes: 4 consecutive features of one key are 4 contiguous bytes
+      const float r0 = a.x * c01.x - bq.x * c01.y, r1 = a.y * c01.z - bq.y * c01.w, r2 = a.z * c23.x - bq.z * c23.y,
+                  r3 = a.w * c23.z - bq.w * c23.w;
+      const float t0 = bq.x * c01.x + a.x * c01.y, t1 = bq.y * c01.z + a.y * c01.w, t2 = bq.z * c23.x + a.z * c23.y,
+                  t3 = bq.w * c23.z + a.w * c23.w;
+      float am = fmaxf(fmaxf(fmaxf(fabsf(r0), fabsf(r1)), fmaxf(fabsf(r2), fabsf(r3))),
+                       fmaxf(fmaxf(fabsf(t0), fabsf(t1)), fmaxf(fabsf(t2), fabsf(t3))));
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+      const float ks = kv8_scale_of(am);
+      uint8_t* k8 = reinterpret_cast<uint8_t*>(kc) + kv8_head_base(g, layer, b, hk);
+      *reinterpret_cast<uint32_t*>(k8 + kv8_k_code(slot, i)) = kv8_pack4(r0, r1, r2, r3, ks);
+      *reinterpret_cast<uint32_t*>(k8 + kv8_k_code(slot, i + 64)) = kv8_pack4(t0, t1, t2, t3, ks);
+      if (w % 16 == 0) *reinterpret_cast<float*>(k8 + kv8_scale(slot)) = ks;
+      return;
+    }
   }
   const uint2 rlo = pack4<E>(a.x * c01.x - bq.x * c01.y, a.y * c01.z - bq.y * c01.w, a.z * c23.x - bq.z * c23.y,
                              a.w * c23.z - bq.w * c23.w);
@@ -257,12 +292,20 @@ int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* c
   dim3 grid(B * t->T, q_heads(g));
   int threads = g.head_dim / 2 <= 64 ? 64 : 128;
   if (is_16bit(dtype) && g.tiled && g.head_dim == 128 && q_heads(g) % 4 == 0 && qkv.n <= kMaxSlots &&
-      qkv.stride % 4 == 0 && (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
-    MDZ_WITH_ELEM16(dtype, (rope_kvwrite_vec_kernel<E><<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(
-                               tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer, seq_len, max_prefix)));
-  else
+      qkv.stride % 4 == 0 && (qkv.split_grid == 0 || qkv.band_cols % 128 == 0)) {
+    if (g.quant)
+      MDZ_WITH_ELEM16(dtype, (rope_kvwrite_vec_kernel<E, true><<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(
+                                 tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer, seq_len, max_prefix)));
+    else
+      MDZ_WITH_ELEM16(dtype, (rope_kvwrite_vec_kernel<E, false><<<dim3(B * t->T, q_heads(g) / 4), 192, 0, st>>>(
+                                 tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer, seq_len, max_prefix)));
+  } else if (g.quant) {
+    MDZ_FAIL(MDZ_EUNSUPPORTED, "8-bit kv rows: the QKV output does not fit the vectorised RoPE kernel (slots %d, stride %lld)",
+             qkv.n, (long long)qkv.stride);
+  } else {
     MDZ_WITH_ELEM(dtype, (rope_kvwrite_kernel<E><<<grid, threads, 0, st>>>(tree, qkv, cs, (E*)q_out, g, (E*)kc, (E*)vc, layer,
                                                                            seq_len, max_prefix)));
+  }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

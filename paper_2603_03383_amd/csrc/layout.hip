@@ -66,8 +66,14 @@ __global__ void kv_copy_kernel(KvGeom g, T* kc, T* vc, int layer, int seq, int p
   }
 }
 
+int launch_kv8_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n, void* k_rows,
+                    void* v_rows, bool to_cache, hipStream_t st);
+int launch_kv8_compact_rows(const KvGeom& g, void* kc, void* vc, int tree, const int32_t* acc_nodes,
+                            const int32_t* accept_len, const int32_t* seq_len, int B, int max_prefix, hipStream_t st);
+
 int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n,
                    void* k_rows, void* v_rows, bool to_cache, hipStream_t st) {
+  if (g.quant) return launch_kv8_copy(dtype, g, kc, vc, layer, seq, pos0, n, k_rows, v_rows, to_cache, st);
   ProfScope prof_(PROF_MISC, st);
   if (n == 0) return MDZ_OK;
   int64_t total = (int64_t)g.n_heads * n * g.head_dim;
@@ -133,7 +139,10 @@ int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, 
   int64_t cols = (int64_t)g.n_layers * g.n_heads * g.head_dim;
   int threads = 256;
   dim3 grid((unsigned)((cols + threads - 1) / threads), B);
-  if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
+  if (g.quant) {
+    int rc = launch_kv8_compact_rows(g, kc, vc, tree, acc_nodes, accept_len, seq_len, B, max_prefix, st);
+    if (rc) return rc;
+  } else if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
     kv_compact_kernel<bf16_t><<<grid, threads, 0, st>>>(g, (bf16_t*)kc, (bf16_t*)vc, tree, acc_nodes, accept_len,
                                                         seq_len, max_prefix);
   else

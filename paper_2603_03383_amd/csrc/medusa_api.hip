@@ -155,7 +155,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.sel_bytes = topk_scratch_bytes((int)rows > B ? (int)rows : B, 16);
   w.sel = take(w.sel_bytes);
   KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (is_16bit(m.dtype) && m.head_dim % 32 == 0) ? 1 : 0,
-           m.n_heads / kv_heads(m)};
+           m.n_heads / kv_heads(m), 0};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
   w.total = off;
   return w;
@@ -181,12 +181,24 @@ static int check_model(const mdz_model_desc* m) {
   return MDZ_OK;
 }
 
+static int check_kv_quant(const mdz_kv_desc* kv) {
+  MDZ_REQUIRE(kv->quant == MDZ_KV_PLAIN || kv->quant == MDZ_KV_FP8E4M3, MDZ_EINVAL, "bad kv quant %d", kv->quant);
+  MDZ_REQUIRE(kv->quant == MDZ_KV_PLAIN || (is_16bit(kv->dtype) && kv->head_dim == 128), MDZ_EUNSUPPORTED,
+              "8-bit kv rows need bf16 or fp16 at the boundary and head_dim 128 (dtype %d, head_dim %d)", kv->dtype,
+              kv->head_dim);
+  return MDZ_OK;
+}
+
 static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int max_prefix) {
   MDZ_REQUIRE(kv != nullptr && kv->k != nullptr && kv->v != nullptr, MDZ_EINVAL, "kv descriptor or its buffers NULL");
   MDZ_REQUIRE(dtype_ok(kv->dtype), MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
   MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
               "kv sizes must be positive");
+  int rc = check_kv_quant(kv);
+  if (rc) return rc;
   if (m) {
+    MDZ_REQUIRE(kv->quant == MDZ_KV_PLAIN || host_tree(m->tree)->T == 64 || host_tree(m->tree)->T == 1, MDZ_EUNSUPPORTED,
+                "8-bit kv rows need a tree of 64 nodes or 1 node");
     MDZ_REQUIRE(kv->dtype == m->dtype && kv->n_heads == kv_heads(*m) && kv->head_dim == m->head_dim &&
                     kv->n_layers >= m->n_layers,
                 MDZ_ESHAPE, "kv cache (L%d H%d hd%d dtype%d) does not match the model (L%d H%d hd%d dtype%d)",
@@ -200,7 +212,7 @@ static int check_kv(const mdz_model_desc* m, const mdz_kv_desc* kv, int B, int m
 // group: query heads per key/value head (1 where only the cache itself is touched)
 static KvGeom geom(const mdz_kv_desc* kv, int group = 1) {
   return KvGeom{kv->n_layers, kv->batch, kv->n_heads, kv->head_dim, kv->cap,
-                (is_16bit(kv->dtype) && kv->head_dim % 32 == 0) ? 1 : 0, group};
+                (is_16bit(kv->dtype) && kv->head_dim % 32 == 0) ? 1 : 0, group, kv->quant == MDZ_KV_FP8E4M3 ? 1 : 0};
 }
 
 // One decoder layer over rows = B*T rows of x.  On entry ws.xn holds RMSNorm(x; g_attn of this layer).  The
@@ -323,6 +335,9 @@ int64_t medusa_kv_bytes(const mdz_kv_desc* kv) {
   MDZ_REQUIRE(dtype_ok(kv->dtype), MDZ_EINVAL, "bad kv dtype %d", kv->dtype);
   MDZ_REQUIRE(kv->n_layers > 0 && kv->batch > 0 && kv->n_heads > 0 && kv->head_dim > 0 && kv->cap > 0, MDZ_EINVAL,
               "kv sizes must be positive");
+  int rc = check_kv_quant(kv);
+  if (rc) return rc;
+  if (kv->quant) return kv8_bytes(geom(kv));
   return kv_elems(geom(kv)) * elem_bytes(kv->dtype);
 }
 

@@ -131,12 +131,13 @@ class DeviceModel:
 
 
 class DeviceKV:
-    """KV cache in the library's own layout."""
+    """KV cache in the library's own layout.  quant="fp8e4m3": 8-bit rows (E4M3 codes + one fp32 scale per row)."""
 
-    def __init__(self, model: DeviceModel, batch: int, cap: int, n_layers: Optional[int] = None):
+    def __init__(self, model: DeviceModel, batch: int, cap: int, n_layers: Optional[int] = None, quant: str = ""):
         d = model.desc
         self.model = model
-        self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, model.kv_heads, d.head_dim, cap, model.dtype)
+        self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, model.kv_heads, d.head_dim, cap, model.dtype,
+                             B.KV_QUANT[quant])
         nbytes = B.medusa_kv_bytes(self.desc)
         self.k = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
         self.v = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)

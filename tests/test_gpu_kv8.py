@@ -1,0 +1,197 @@
+"""GPU parity with 8-bit KV cache rows (the KV compression the paper's Sections 4.2 and 5 point to; format stated in
+oracle/kv8.py and include/medusa.h): E4M3 codes + one fp32 scale per row, written by medusa_kv_write and by the
+kernels that produce the tree rows, read by the attention kernels, moved by kv_compact.
+
+Bars: codes and scales bit-exact wherever both sides quantise the same fp32 input (medusa_kv_write, compaction);
+rows the kernels produce from their own arithmetic differ from the oracle's by the 16-bit bound or, where the small
+upstream difference crosses a rounding boundary of the 8-bit grid, by one grid step (2^-3 relative at most), for a small
+fraction of elements; layer outputs and logits within the storage dtype's bound."""
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+import paper_2603_03383_amd as P
+from oracle import kv8
+from oracle import medusa as O
+from oracle import tree as OT
+from tests import gpu_util as G
+from tests import util as U
+from tests.test_gpu_parity import TOL, _i32, _scale, check_argmax_near_tie, _layer_case
+from tests.test_gpu_gqa import two_layer_step_case
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(dtype, n_kv_heads=2, L=2):
+    return P.DeviceModel(d=4 * 128, n_heads=4, head_dim=128, ffn=64, vocab=64, n_layers=L, dtype=dtype, tree="tree64",
+                         n_kv_heads=n_kv_heads)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_write_then_read_is_the_oracles_round_trip_bit_for_bit(dtype):
+    """Rows of several magnitudes, a zero row, exact ties of the 8-bit grid, subnormal codes, negative values that
+    round to zero: medusa_kv_write + medusa_kv_read must equal round_to_storage(value(code) * scale) of the oracle."""
+    dm = _model(dtype)
+    H, hd, n, pos0 = 2, 128, 70, 29                      # rows 29..98: three blocks, ragged on both ends
+    kv = P.DeviceKV(dm, batch=2, cap=128, quant="fp8e4m3")
+    assert P.medusa_kv_bytes(kv.desc) == 2 * 2 * 2 * (128 // 32) * (32 * 128 + 32 * 4)
+    k = W.normal(11, "kv8.wr.k", (H, n, hd), 1.0, dm.tdtype).float()
+    v = W.normal(11, "kv8.wr.v", (H, n, hd), 1.0, dm.tdtype).float()
+    k[0, 1] *= 1e-3; k[0, 2] *= 300.0; k[1, 3] = 0.0
+    grid = torch.tensor(kv8.e4m3_table()[:0x7F], dtype=torch.float32)
+    ties = (grid[:-1] + grid[1:]) / 2                    # exact in bf16/fp16? keep those that are
+    row = torch.zeros(hd); row[0] = 448.0; row[1:127] = ties[:126] * torch.tensor([1.0, -1.0]).repeat(63)
+    v[0, 4] = row                                         # scale exactly 1: the values hit the ties themselves
+    tiny = torch.zeros(hd); tiny[0] = 448.0; tiny[1:9] = torch.tensor([2.0 ** -9, -2.0 ** -9, 2.0 ** -10, -2.0 ** -10, 3 * 2.0 ** -10,
+                                                                       2.0 ** -11, -2.0 ** -11, 2.0 ** -7])
+    v[1, 5] = tiny
+    k, v = k.to(dm.tdtype), v.to(dm.tdtype)               # exact storage values (ties that are not representable move off the tie)
+    kv.write(1, 1, pos0, k, v)
+    gk, gv = kv.read(1, 1, pos0, n)
+    ek = O.round_to_storage(kv8.roundtrip_rows(U.to_np(k)), dtype)
+    ev = O.round_to_storage(kv8.roundtrip_rows(U.to_np(v)), dtype)
+    np.testing.assert_array_equal(U.to_np(gk), ek)
+    np.testing.assert_array_equal(U.to_np(gv), ev)
+    # untouched slots and the other sequence / layer stay zero
+    z, _ = kv.read(1, 1, 0, pos0)
+    assert float(z.abs().max()) == 0.0
+    z, _ = kv.read(0, 0, 0, 128)
+    assert float(z.abs().max()) == 0.0
+
+
+# Two runs that both quantise do not agree to the 16-bit bound: where the small upstream difference (16-bit rounding of
+# the normalised input, relative size u = 2^-9 for bf16, 2^-12 for fp16) moves a value across a rounding boundary of the
+# 8-bit grid, the code flips to its neighbour and that element changes by a whole grid step (relative size D between
+# 2^-4 and 2^-3) instead of u.  A flip happens with probability ~ u / D and costs D, so the flips add an error of
+# relative size sqrt(u / D) * D = sqrt(u * D) where the 16-bit path has u: it shrinks with the square root of the
+# storage precision only.  Measured on the CPU with the oracle alone (bf16-rounded against exact layer input, S = 0,
+# where a node sees 5 keys at most and nothing averages out): 1.1e-2 of scale against 3.9e-3 without quantisation.
+# Bound for the direct comparison: 2 * sqrt(u * 2^-3.5) (bf16 2.6e-2, fp16 9.3e-3; measured up to 1.7e-2 and 7.4e-3,
+# ratio sqrt(8) as the model says).  The arithmetic itself is held to the 16-bit bound by a second comparison in which
+# the oracle is given the rows the GPU wrote (substituted_reference).
+KV8_DIRECT_TOL = {"bf16": 2 * (2.0 ** -9 * 2.0 ** -3.5) ** 0.5, "fp16": 2 * (2.0 ** -12 * 2.0 ** -3.5) ** 0.5}
+
+
+def substituted_reference(w, S_list, r, x_seed):
+    """The oracle's layer output when its cache-write step stores the rows the GPU stored (read back through
+    medusa_kv_read) instead of its own quantisation of its own K / V: what remains is the attention arithmetic."""
+    tree = U.oracle_tree(w)
+    T = tree["T"]
+    cfg = U.oracle_cfg(w)
+    lw = U.oracle_layer(w, 0, device=G.DEV)
+    x = W.hidden_state(w, x_seed, len(S_list) * T, device=G.DEV).float().cpu().numpy().astype(np.float64)
+    outs = []
+    real = kv8.roundtrip_rows
+    for b, S in enumerate(S_list):
+        k, v = r["kv"].read(0, b, S, T)
+        queue = [U.to_np(k).astype(np.float64), U.to_np(v).astype(np.float64)]
+        kc, vc = r["caches"][b]
+        kc, vc = kc.copy(), vc.copy()
+        kv8.roundtrip_rows = lambda rows: queue.pop(0)       # called for K, then for V, by the layer's cache write
+        try:
+            outs.append(O.tree_verify_layer(x[b * T:(b + 1) * T], lw, kc, vc, S, tree, cfg))
+        finally:
+            kv8.roundtrip_rows = real
+        assert not queue
+    return np.concatenate(outs)
+
+
+def check_layer_kv8(r, S_list, w, x_seed):
+    tol = TOL[w.dtype]
+    err = np.abs(r["x"] - r["ref"]).max()
+    assert err <= KV8_DIRECT_TOL[w.dtype] * _scale(r["ref"]), f"layer output error {err} vs scale {_scale(r['ref'])}"
+    ref2 = substituted_reference(w, S_list, r, x_seed)
+    err2 = np.abs(r["x"] - ref2).max()
+    assert err2 <= tol * _scale(ref2), f"layer output error with the GPU's rows substituted {err2} vs scale {_scale(ref2)}"
+    T = r["T"]
+    worst_frac = 0.0
+    for b, S in enumerate(S_list):
+        k, v = r["kv"].read(0, b, S, T)
+        kc, vc = r["caches"][b]
+        for got, ref in ((U.to_np(k), kc[:, S:]), (U.to_np(v), vc[:, S:])):
+            ref16 = O.round_to_storage(ref, w.dtype)
+            d = np.abs(got - ref16)
+            near = d <= tol * np.abs(ref).max(-1, keepdims=True)             # same code, or a neighbour at small magnitude
+            step = d <= 0.13 * np.abs(ref16) + tol * np.abs(ref).max(-1, keepdims=True)   # the neighbouring code: one grid step
+            assert np.all(near | step), float((d / (np.abs(ref16) + 1e-9)).max())
+            worst_frac = max(worst_frac, 1.0 - near.mean())
+        if S:                                                                 # prefix rows untouched, bit for bit
+            k0, v0 = r["kv"].read(0, b, 0, S)
+            assert np.array_equal(U.to_np(k0), O.round_to_storage(kc[:, :S], w.dtype))
+            assert np.array_equal(U.to_np(v0), O.round_to_storage(vc[:, :S], w.dtype))
+    assert worst_frac < 0.10, worst_frac
+    return err / _scale(r["ref"]), err2 / _scale(ref2), worst_frac
+
+
+@pytest.mark.parametrize("S_list,max_prefix", [([0], 0), ([77], 100), ([1024], 1024), ([300, 0, 45], 300), ([5000], 5003)])
+@pytest.mark.parametrize("kv_heads,dtype", [(0, "bf16"), (8, "bf16"), (8, "fp16")], ids=["mha-bf16", "gqa8-bf16", "gqa8-fp16"])
+def test_7b_width_layer_8bit_rows(S_list, max_prefix, kv_heads, dtype):
+    w = W.CONFIGS["cfg2_layer_bf16"].with_(name="layer_kv8", dtype=dtype, n_kv_heads=kv_heads, prefix=tuple(S_list),
+                                            kv_quant="fp8e4m3")
+    r = _layer_case(w, S_list, max_prefix, x_seed="kv8_layer_x")
+    rel, rel2, frac = check_layer_kv8(r, S_list, w, "kv8_layer_x")
+    print(f"kv8 layer {S_list} kv_heads={kv_heads} {dtype}: err/scale {rel:.3e}, with the GPU's rows substituted {rel2:.3e}, "
+          f"elements a visible grid step off {frac:.3%}")
+
+
+@pytest.mark.parametrize("S_list,max_prefix", [([0, 33, 1000], 1000), ([4097], 4100)])
+def test_7b_width_autoregressive_layer_8bit_rows(S_list, max_prefix):
+    w = W.CONFIGS["cfg2_layer_bf16"].with_(name="ar_layer_kv8", tree=W.TREE1, n_kv_heads=8, prefix=tuple(S_list),
+                                            kv_quant="fp8e4m3")
+    r = _layer_case(w, S_list, max_prefix, x_seed="kv8_ar_x")
+    rel, rel2, frac = check_layer_kv8(r, S_list, w, "kv8_ar_x")
+    print(f"kv8 AR layer {S_list}: err/scale {rel:.3e}, substituted {rel2:.3e}, a visible grid step off {frac:.3%}")
+
+
+def test_two_layer_step_8bit_rows():
+    two_layer_step_case(W.CONFIGS["cfg3_step_1k"].with_(name="step_kv8", n_layers=2, n_kv_heads=8, kv_quant="fp8e4m3"))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_kv_compact_moves_codes_and_scales_bit_exact(dtype):
+    spec = W.TREE64
+    tree = OT.build_tree(spec.caps, spec.budgets)
+    T, K = tree["T"], tree["K"]
+    L, H, hd, Bn = 3, 2, 128, 5
+    S_list = [0, 7, 33, 100, 64]
+    max_prefix = 100
+    cap = max_prefix + T
+    dm = _model(dtype, n_kv_heads=H, L=L)
+    kv = P.DeviceKV(dm, batch=Bn, cap=cap, quant="fp8e4m3")
+    kcs, vcs = [], []
+    for b in range(Bn):
+        kb, vb = [], []
+        for l in range(L):
+            k = W.normal(5, f"cmp8.k.{b}.{l}", (H, cap, hd), 1.0 + b, dm.tdtype)
+            v = W.normal(5, f"cmp8.v.{b}.{l}", (H, cap, hd), 0.5 + l, dm.tdtype)
+            kv.write(l, b, 0, k, v)
+            kb.append(kv8.roundtrip_rows(U.to_np(k))); vb.append(kv8.roundtrip_rows(U.to_np(v)))
+        kcs.append(kb); vcs.append(vb)
+    rows = [0, 37, 20, 30, 36]
+    lens = [1, 5, 3, 4, 2]
+    acc_nodes = np.full((Bn, K + 1), -1, np.int32)
+    for b in range(Bn):
+        A = min(lens[b], int((tree["retrieve"][rows[b]] >= 0).sum()))
+        lens[b] = A
+        acc_nodes[b, :A] = tree["retrieve"][rows[b], :A]
+    seq_len = _i32(S_list)
+    slots = torch.zeros(Bn, K + 1, dtype=torch.int32, device=G.DEV)
+    P.kv_compact(kv.desc, P.MDZ_TREE_64, _i32(acc_nodes), _i32(lens), seq_len, slots, Bn, max_prefix)
+    torch.cuda.synchronize()
+    for b in range(Bn):
+        src, S2 = O.kv_compact(kcs[b], vcs[b], S_list[b], acc_nodes[b], lens[b])
+        assert slots[b].cpu().numpy().tolist() == src.tolist() and int(seq_len[b]) == S2
+        for l in range(L):
+            k, v = kv.read(l, b, 0, cap)
+            assert np.array_equal(U.to_np(k), O.round_to_storage(kcs[b][l], dtype))
+            assert np.array_equal(U.to_np(v), O.round_to_storage(vcs[b][l], dtype))
+
+
+def test_unsupported_shapes_are_refused():
+    dm = P.DeviceModel(d=256, n_heads=4, head_dim=64, ffn=64, vocab=64, n_layers=1, dtype="bf16", tree="tree15")
+    with pytest.raises(P.MedusaError):
+        P.DeviceKV(dm, batch=1, cap=64, quant="fp8e4m3")            # head_dim 64
+    dm32 = P.DeviceModel(d=512, n_heads=4, head_dim=128, ffn=64, vocab=64, n_layers=1, dtype="fp32", tree="tree64")
+    with pytest.raises(P.MedusaError):
+        P.DeviceKV(dm32, batch=1, cap=128, quant="fp8e4m3")         # fp32 boundary

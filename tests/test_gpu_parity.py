@@ -193,14 +193,14 @@ def _layer_case(w, S_list, max_prefix, x_seed="layer_x"):
     cfg = U.oracle_cfg(w)
     lw = U.oracle_layer(w, 0, device=G.DEV)
     dm = G.device_model(w.with_(vocab=1024), heads=False, n_layers=1)          # vocab irrelevant for one layer
-    kv = P.DeviceKV(dm, batch=Bn, cap=max_prefix + T, n_layers=1)
+    kv = P.DeviceKV(dm, batch=Bn, cap=max_prefix + T, n_layers=1, quant=w.kv_quant)
     x = W.hidden_state(w, x_seed, Bn * T, device=G.DEV).float()                # bf16-valued fp32 rows
     x_ref = x.cpu().numpy().astype(np.float64)
     outs, caches = [], []
     for b, S in enumerate(S_list):
         k, v = W.prefix_kv(w.with_(prefix=tuple(S_list)), 0, b, G.DEV)
         kc = np.zeros((w.kv_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
-        kc[:, :S] = U.to_np(k); vc[:, :S] = U.to_np(v)
+        kc[:, :S] = U.stored_rows(w, U.to_np(k)); vc[:, :S] = U.stored_rows(w, U.to_np(v))
         if S:
             kv.write(0, b, 0, k, v)
         outs.append(O.tree_verify_layer(x_ref[b * T:(b + 1) * T], lw, kc, vc, S, tree, cfg))

@@ -16,7 +16,7 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 
 def oracle_cfg(w: W.Workload, dtype=None) -> dict:
     return dict(n_layers=w.n_layers, d=w.d, n_heads=w.n_heads, n_kv_heads=w.kv_heads, head_dim=w.head_dim, ffn=w.ffn,
-                vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=dtype or w.dtype)
+                vocab=w.vocab, rms_eps=w.rms_eps, rope_base=w.rope_base, dtype=dtype or w.dtype, kv_quant=w.kv_quant)
 
 
 def oracle_tree(w: W.Workload) -> dict:
@@ -42,6 +42,14 @@ def oracle_model(w: W.Workload, device="cpu", heads=True, dtype=None) -> dict:
     return m
 
 
+def stored_rows(w: W.Workload, rows: np.ndarray) -> np.ndarray:
+    """What the cache holds after rows (exact storage-dtype values) were written into it."""
+    if w.kv_quant == "fp8e4m3":
+        from oracle import kv8
+        return kv8.roundtrip_rows(rows)
+    return rows.astype(np.float64)
+
+
 def oracle_prefix_cache(w: W.Workload, seq: int, cap: int, device="cpu"):
     """Per-layer [H,cap,hd] float64 caches whose first S rows are the workload's random prefix KV."""
     cfg = oracle_cfg(w)
@@ -49,8 +57,8 @@ def oracle_prefix_cache(w: W.Workload, seq: int, cap: int, device="cpu"):
     S = w.prefix[seq]
     for l in range(w.n_layers):
         k, v = W.prefix_kv(w, l, seq, device)
-        kc[l][:, :S] = to_np(k)
-        vc[l][:, :S] = to_np(v)
+        kc[l][:, :S] = stored_rows(w, to_np(k))
+        vc[l][:, :S] = stored_rows(w, to_np(v))
     return kc, vc
 
 

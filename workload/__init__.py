@@ -163,6 +163,7 @@ class Workload:
     weight_std: float = 0.02
     seed: int = BASE_SEED
     n_kv_heads: int = 0        # key/value heads (grouped-query attention); 0 = n_heads (plain multi-head attention)
+    kv_quant: str = ""         # "" | "fp8e4m3": cache rows stored as 8-bit codes with one fp32 scale per row
 
     @property
     def kv_heads(self) -> int:
