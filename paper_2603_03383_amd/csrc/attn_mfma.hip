@@ -29,6 +29,7 @@ constexpr int kHD = 128;         // head_dim
 constexpr int kTQ = 64;          // queries (tree nodes)
 constexpr int kOPad = kTQ + 2;   // LDS row stride of the merge buffer (floats): 66 keeps its writes and reads conflict free
 constexpr int kQRow = kHD * 2 + 16;  // bytes per staged Q row
+constexpr float kLazyLog2 = 8.f;  // see the key loop: how far a block's maximum may exceed the running reference
 constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -250,22 +251,23 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[tt][u][r] = 0.f;
 
-  // K is double buffered one block ahead; V of a block is requested when its scores start, so its
-  // latency hides behind the 16 score MFMAs and the softmax arithmetic (and the other waves of the CU).
-  u32x4 kb[2][8];
-  auto load_k = [&](int blk, u32x4 (&kd)[8]) {  // 8-bit rows: kd[0..3] codes, kd[4..7] the lane's 16 scales
+  // K and V are both double buffered one block ahead of the block being multiplied, and every load is
+  // unconditional (past the wave's last block it repeats that block and the result is not used): the wait counters
+  // are in-order, so a wave then keeps a whole block (16 KiB of 16-bit rows) in flight while it works on the
+  // previous one, which is what the HBM latency asks for at one wave per SIMD.
+  u32x4 kb[2][8], vb[2][8];
+  auto load_kv = [&](int blk, u32x4 (&kd)[8], u32x4 (&vd)[8]) {  // 8-bit rows: [0..3] codes, [4..7] the lane's 16 scales
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       kd[i] = (Q8 && i >= 4) ? ks_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : kp[(int64_t)blk * kBlkPieces + i * 64];
-  };
-  auto process = [&](int blk, const u32x4 (&kd)[8]) {
-    // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
-    // than in 64 registers per lane that this kernel does not have to spare.
-    asm volatile("" ::: "memory");
-    u32x4 vd[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       vd[i] = (Q8 && i >= 4) ? vs_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : vp[(int64_t)blk * kBlkPieces + i * 64];
+  };
+  auto process = [&](int blk, const u32x4 (&kd)[8], const u32x4 (&vd)[8]) {
+    // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
+    // than in 64 registers per lane that this kernel does not have to spare.
+    asm volatile("" ::: "memory");
     f32x16 sc[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
@@ -289,25 +291,35 @@ __global__ void __launch_bounds__(256)
     u32x4 pf[2][2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      uint32_t vis = 0xFFFFFFFFu;
-      if (need_mask) {
-        uint32_t pre = rel0 >= 0 ? 0u : (0xFFFFFFFFu >> (32 + rel0));          // keys below S (rel0 in [-31,-1])
-        uint64_t tr = rel0 >= 0 ? (mq[u] >> rel0) : (mq[u] << (-rel0));        // rel0 in [-31, 63]
-        vis = (pre | (uint32_t)tr) >> (4 * gh);
-      }
       float bmax = -INFINITY;
+      // register r is key 8*(r/4) + 4*gh + r%4 of the block; its scale is component r%4 of scale piece r/4
+      if (need_mask) {  // wave-uniform branch: only the (at most three) blocks that hold tree slots pay for the mask
+        const uint32_t pre = rel0 >= 0 ? 0u : (0xFFFFFFFFu >> (32 + rel0));          // keys below S (rel0 in [-31,-1])
+        const uint64_t tr = rel0 >= 0 ? (mq[u] >> rel0) : (mq[u] << (-rel0));        // rel0 in [-31, 63]
+        const uint32_t vis = (pre | (uint32_t)tr) >> (4 * gh);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        // register r is key 8*(r/4) + 4*gh + r%4 of the block; its scale is component r%4 of scale piece r/4
-        float s = sc[u][r] * (Q8 ? __uint_as_float(kd[4 + (r >> 2)][r & 3]) * scale_log2 : scale_log2);
-        s = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s : -INFINITY;
-        sc[u][r] = s;
-        bmax = fmaxf(bmax, s);
+        for (int r = 0; r < 16; ++r) {
+          float s = sc[u][r] * (Q8 ? __uint_as_float(kd[4 + (r >> 2)][r & 3]) * scale_log2 : scale_log2);
+          s = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s : -INFINITY;
+          sc[u][r] = s;
+          bmax = fmaxf(bmax, s);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float s = sc[u][r] * (Q8 ? __uint_as_float(kd[4 + (r >> 2)][r & 3]) * scale_log2 : scale_log2);
+          sc[u][r] = s;
+          bmax = fmaxf(bmax, s);
+        }
       }
       bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-      float m_new = fmaxf(m_run[u], bmax);
-      float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      alpha[u] = fast_exp2(m_run[u] - m_safe);
+      // The running reference m_run only has to keep exp2(s - m_run) in range, it need not be the maximum: it is
+      // moved (and the accumulators rescaled: 128 registers through the vector ALU) only when a block's maximum
+      // exceeds it by more than 2^kLazyLog2, so probabilities stay below 2^kLazyLog2 and, in a long prefix, almost
+      // no block rescales.  o, l and m stay consistent, so the merges below need no change.
+      const float m_new = bmax > m_run[u] + kLazyLog2 ? bmax : m_run[u];
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      alpha[u] = m_new == m_run[u] ? 1.f : fast_exp2(m_run[u] - m_safe);
       float sum = 0.f;
       uint32_t pk[8];
 #pragma unroll
@@ -340,20 +352,21 @@ __global__ void __launch_bounds__(256)
       }
   };
 
-  int blk = blk_begin + wave;
-  if (blk < blk_end) {
-    load_k(blk, kb[0]);
-    while (true) {
-      bool more = blk + 4 < blk_end;
-      if (more) load_k(blk + 4, kb[1]);
-      process(blk, kb[0]);
-      if (!more) break;
-      blk += 4;
-      more = blk + 4 < blk_end;
-      if (more) load_k(blk + 4, kb[0]);
-      process(blk, kb[1]);
-      if (!more) break;
-      blk += 4;
+  // this wave's blocks: blk_begin + wave, + 4, ... ; two per trip so that the buffers alternate statically
+  const int n_mine = blk_begin + wave < blk_end ? (blk_end - blk_begin - wave + 3) >> 2 : 0;
+  if (n_mine > 0) {
+    const int first = blk_begin + wave, last = first + 4 * (n_mine - 1);
+    load_kv(first, kb[0], vb[0]);
+    for (int it = 0; it < n_mine; it += 2) {
+      const int blk = first + 4 * it;
+      load_kv(min(blk + 4, last), kb[1], vb[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      process(blk, kb[0], vb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_kv(min(blk + 8, last), kb[0], vb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + 1 < n_mine) process(blk + 4, kb[1], vb[1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -459,15 +472,16 @@ bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
 
 // Key-splits per (sequence, head).  fused: the kernel starts from the QKV partial sums, so one split is the tree
 // split and the rest share the prefix: at most as many as keep every workgroup resident at once (one per CU: the
-// merge buffer takes most of a CU's LDS), and one per ten prefix blocks: the tree split's reduce-write-read
-// chain lasts about as long as ten blocks of a prefix split, and more workgroups only slow every reduce down.
+// merge buffer takes most of a CU's LDS).  Every further split costs about a microsecond per layer (its reduce of
+// the Q partial sums, its share of the merge) and saves the blocks it takes off the others, so the best count grows
+// with the square root of the prefix: measured best 1 / 3 / 5 / 8 splits at prefixes 128 / 1K / 4K / 16K.
 static int attn_splits(int B, int n_heads, int max_prefix, bool fused) {
   static const char* env = getenv("MDZ_ATTN_SPLITS");  // development knob
   if (env && atoi(env) > 0) return atoi(env) > 32 ? 32 : atoi(env);
   const int pairs = B * n_heads;
   if (fused) {
     int ps = 256 / pairs - 1;
-    const int by_len = ((max_prefix >> 5) + 5) / 10;
+    const int by_len = (int)sqrtf((float)(max_prefix >> 5) / 8.0f);
     if (ps > by_len) ps = by_len;
     if (ps > 31) ps = 31;
     return ps >= 1 ? ps + 1 : 1;

@@ -88,11 +88,10 @@ template <typename E>
 struct Elem16;
 template <>
 struct Elem16<bf16_t> {
-  __device__ static inline uint32_t pack2(float a, float b) {  // round to nearest even, finite inputs
-    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7FFFu + ((ua >> 16) & 1u);
-    ub += 0x7FFFu + ((ub >> 16) & 1u);
-    return (ua >> 16) | (ub & 0xFFFF0000u);
+  __device__ static inline uint32_t pack2(float a, float b) {  // round to nearest even: one v_cvt_pk_bf16_f32
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{a, b}, v2));
   }
   __device__ static inline float lo(uint32_t w) { return __uint_as_float(w << 16); }
   __device__ static inline float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
