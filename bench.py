@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--prefix", type=int, default=None, help="override the workload's prefix length (every sequence)")
     ap.add_argument("--kv8", action="store_true", help="8-bit KV cache rows (E4M3 codes + one fp32 scale per row)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="leave out the autoregressive baseline and the chained loop (profiling runs: only the timed steps are traced)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); run with --gpus 1",
@@ -208,7 +210,7 @@ def main():
 
     # the autoregressive baseline (Section 4.1): the same weights and prefix, the single-node tree, timed the same way
     ar = None
-    if not layer_only:
+    if not layer_only and not args.skip_extras:
         dm_ar = dm.view_with_tree("tree1")
         buf_ar = P.StepBuffers(dm_ar, Bn, max_prefix)
         h_ar = hidden
@@ -240,7 +242,7 @@ def main():
     # the chained on-device loop (Section 3.2's device-resident, static-shape decode): N steps back to back, each
     # step's root / hidden / lengths taken from the previous one on the device; eager launches vs one HIP graph replayed
     chain = None
-    if not layer_only and with_heads:
+    if not layer_only and with_heads and not args.skip_extras:
         n_chain = 16
         cap_chain = max(w.prefix) + n_chain * (w.n_medusa + 1)
         kv_c = P.DeviceKV(dm, batch=Bn, cap=cap_chain + T, quant=w.kv_quant)
