@@ -400,12 +400,14 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   const int64_t ld = (int64_t)(t->K + 1) * V;  // row stride of the [B][K+1][V] logits
   float* hl = head_logits_opt ? head_logits_opt : (float*)(wsb + L.hlogits);
   if ((rc = launch_gather_rows(m.dtype, hidden, src_row, B, Tsrc, m.d, h, st))) return rc;
+  // the heads' candidates are selected in one pair of launches after the last GEMM where the shape allows it
+  const bool batched = heads_select_supported(m.tree, B, m.vocab, L.sel_bytes);
   // slot 0: root token
   if (root_token) {
-    if ((rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
+    if (!batched && (rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;
   } else {
     if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
-    if ((rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, wsb + L.sel, L.sel_bytes, st))) return rc;
+    if (!batched && (rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, wsb + L.sel, L.sel_bytes, st))) return rc;
   }
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
@@ -414,10 +416,12 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
     if ((rc = launch_head_residual(m.dtype, h, pr, b1, z, B, m.d, st))) return rc;
     float* lk = hl + (int64_t)(k + 1) * V;
     if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
-    if ((rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, wsb + L.sel, L.sel_bytes, st)))
+    if (!batched &&
+        (rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, wsb + L.sel, L.sel_bytes, st)))
       return rc;
     seg += t->caps[k];
   }
+  if (batched && (rc = launch_heads_select(m.tree, hl, B, m.vocab, root_token, cand_flat, wsb + L.sel, st))) return rc;
   return launch_tree_tokens(m.tree, cand_flat, tree_tokens, B, st);
 }
 

@@ -163,6 +163,120 @@ int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t
   return MDZ_OK;
 }
 
+// ---- all heads of all sequences in one pair of launches --------------------------------------------------------
+// Row (b, j) of logits [B][K+1][V]: j = 0 is the base LM head (its argmax is the root candidate unless the caller
+// gave root tokens), j = 1..K Medusa head j with its own top-k size caps[j-1].  The picks go straight to their
+// segment of cand_flat [B][n_cand] = [root | head 1 | .. | head K].  Same two stages and the same total order as
+// above, so the result equals per-head launches; it replaces 2 (K + 1) launches of ~10 us each by 2.
+constexpr int kHeadsMaxK = 16;  // largest per-head top-k the stage-1 buffer is laid out for
+__device__ inline int heads_row_k(const TreeTables& t, int j, bool have_root) { return j == 0 ? (have_root ? 0 : 1) : t.caps[j - 1]; }
+
+__global__ void __launch_bounds__(256) heads_topk_stage1_kernel(int tree, const float* __restrict__ logits, int V,
+                                                                bool have_root, float* __restrict__ cand_v,
+                                                                int32_t* __restrict__ cand_i) {
+  __shared__ Best red[4];
+  const TreeTables& t = c_trees[tree];
+  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
+  const int k = heads_row_k(t, row % (t.K + 1), have_root);
+  if (k == 0) return;
+  const int per = (V + n_chunks - 1) / n_chunks;
+  const int c0 = chunk * per, c1 = min(c0 + per, V);
+  const float* src = logits + (int64_t)row * V;
+  float v[kSelPerThread];
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    int i = c0 + threadIdx.x + j * 256;
+    v[j] = i < c1 ? src[i] : -INFINITY;
+  }
+  float pv = INFINITY;
+  int pi = -1;
+  for (int p = 0; p < k; ++p) {
+    Best b{-INFINITY, kNoIndex};
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+      int i = c0 + threadIdx.x + j * 256;
+      bool ok = i < c1 && (p == 0 || precedes(pv, pi, v[j], i));
+      if (ok && precedes(v[j], i, b.v, b.i)) {
+        b.v = v[j];
+        b.i = i;
+      }
+    }
+    b = block_best_256(b, red);
+    if (threadIdx.x == 0) {
+      int64_t o = ((int64_t)row * n_chunks + chunk) * kHeadsMaxK + p;
+      cand_v[o] = b.v;
+      cand_i[o] = b.i;
+    }
+    pv = b.v;
+    pi = b.i;
+  }
+}
+
+__global__ void __launch_bounds__(256) heads_topk_stage2_kernel(int tree, const float* __restrict__ cand_v,
+                                                                const int32_t* __restrict__ cand_i, int n_chunks,
+                                                                const int32_t* __restrict__ root_token,
+                                                                int32_t* __restrict__ cand_flat) {
+  __shared__ Best red[4];
+  const TreeTables& t = c_trees[tree];
+  const int row = blockIdx.x, b = row / (t.K + 1), j = row % (t.K + 1);
+  int seg = 0;  // start of row j's segment in the flat candidate buffer
+  for (int i = 1; i <= j; ++i) seg += i == 1 ? 1 : t.caps[i - 2];
+  int32_t* out = cand_flat + (int64_t)b * t.n_cand + seg;
+  const int k = heads_row_k(t, j, root_token != nullptr);
+  if (k == 0) {
+    if (threadIdx.x == 0) out[0] = root_token[b];
+    return;
+  }
+  const float* cv = cand_v + (int64_t)row * n_chunks * kHeadsMaxK;
+  const int32_t* ci = cand_i + (int64_t)row * n_chunks * kHeadsMaxK;
+  const int n = n_chunks * k;
+  float pv = INFINITY;
+  int pi = -1;
+  for (int p = 0; p < k; ++p) {
+    Best bst{-INFINITY, kNoIndex};
+    for (int e = threadIdx.x; e < n; e += 256) {
+      const int at = (e / k) * kHeadsMaxK + e % k;
+      float v = cv[at];
+      int i = ci[at];
+      bool ok = i != kNoIndex && (p == 0 || precedes(pv, pi, v, i));
+      if (ok && precedes(v, i, bst.v, bst.i)) {
+        bst.v = v;
+        bst.i = i;
+      }
+    }
+    bst = block_best_256(bst, red);
+    if (threadIdx.x == 0) out[p] = bst.i == kNoIndex ? -1 : bst.i;
+    pv = bst.v;
+    pi = bst.i;
+  }
+}
+
+// true if launch_heads_select can serve this shape with this much scratch (else the caller selects head by head)
+bool heads_select_supported(int tree, int B, int V, int64_t scratch_bytes) {
+  const TreeTables* t = host_tree(tree);
+  int kmax = 1;
+  for (int k = 0; k < t->K; ++k) kmax = t->caps[k] > kmax ? t->caps[k] : kmax;
+  const int n_chunks = sel_chunks(V);
+  return V >= 8192 && n_chunks <= kSelMaxChunks && kmax <= kHeadsMaxK &&
+         scratch_bytes >= (int64_t)B * (t->K + 1) * n_chunks * kHeadsMaxK * 8;
+}
+
+int launch_heads_select(int tree, const float* logits, int B, int V, const int32_t* root_token, int32_t* cand_flat,
+                        void* scratch, hipStream_t st) {
+  ProfScope prof_(PROF_SELECT, st);
+  const TreeTables* t = host_tree(tree);
+  const int rows = B * (t->K + 1);
+  if (rows == 0) return MDZ_OK;
+  const int n_chunks = sel_chunks(V);
+  float* cv = (float*)scratch;
+  int32_t* ci = (int32_t*)(cv + (int64_t)rows * n_chunks * kHeadsMaxK);
+  heads_topk_stage1_kernel<<<dim3(n_chunks, rows), 256, 0, st>>>(tree, logits, V, root_token != nullptr, cv, ci);
+  MDZ_LAUNCH_CHECK();
+  heads_topk_stage2_kernel<<<rows, 256, 0, st>>>(tree, cv, ci, n_chunks, root_token, cand_flat);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
 int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,
                   hipStream_t st) {
   return launch_topk(logits, rows, V, ld, 1, out, 1, scratch, scratch_bytes, st);
