@@ -27,10 +27,8 @@ typedef u32x4_t u32x4;
 
 constexpr int kHD = 128;         // head_dim
 constexpr int kTQ = 64;          // queries (tree nodes)
-constexpr int kOPad = kTQ + 2;   // LDS row stride of the merge buffer (floats): 66 keeps its writes and reads conflict free
 constexpr int kQRow = kHD * 2 + 16;  // bytes per staged Q row
 constexpr float kLazyLog2 = 8.f;  // see the key loop: how far a block's maximum may exceed the running reference
-constexpr int kAttnLdsBytes = 4 * kHD * kOPad * 4 + 4 * 2 * kTQ * 4;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -104,8 +102,12 @@ __device__ inline void rope16(const float* cs_row, int seg, float (&lo)[16], flo
 // cos/sin table cs [row][64][2]), keeps q in LDS, and — if its key range reaches the tree slots — writes the 64
 // tree rows of K and V of its head into the cache before reading them back like any other key.  Workgroups of
 // the same head that both reach the tree slots write identical values.
-template <typename E, bool Q8>
-__global__ void __launch_bounds__(256)
+// NU = 2: a workgroup carries all 64 queries (two groups of 32).  NU = 1: it carries 32 of them, the two halves of a
+// (sequence, head, split) being two workgroups (blockIdx.z = 2 * sequence + half): half the accumulators, so two
+// workgroups share a CU and twice as many loads are in flight per CU, at the price of K and V passing through the
+// CU twice (the second time from L2: the halves are a multiple of 8 workgroups apart, i.e. on one XCD).
+template <typename E, bool Q8, int NU>
+__global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
     attn_tree_mfma_kernel(int tree, const E* __restrict__ q, const Partials qkv, const float* __restrict__ cs,
                           KvGeom g, E* __restrict__ kc, E* __restrict__ vc, int layer,
                           const int32_t* __restrict__ seq_len, int max_prefix, E* __restrict__ att_out,
@@ -114,7 +116,11 @@ __global__ void __launch_bounds__(256)
   const TreeTables& t = c_trees[tree];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qi = lane & 31, gh = lane >> 5;
-  const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y, b = blockIdx.z;
+  constexpr int kQW = 32 * NU;          // queries of this workgroup
+  constexpr int kOPadN = kQW + 2;       // LDS row stride of the merge buffer (floats): conflict-free writes and reads
+  const int split = blockIdx.x, n_splits = gridDim.x, h = blockIdx.y;
+  const int b = NU == 2 ? blockIdx.z : blockIdx.z >> 1;
+  const int q0 = NU == 2 ? 0 : (blockIdx.z & 1) * 32;  // first query of this workgroup
   const int hk = h / g.group;  // the key/value head that query head h reads (grouped-query attention)
   const int d = q_heads(g) * kHD, dkv = g.n_heads * kHD;
   const int S = min(max(seq_len[b], 0), max_prefix);
@@ -135,39 +141,37 @@ __global__ void __launch_bounds__(256)
   uint8_t* q_lds = reinterpret_cast<uint8_t*>(lds);
   if (qkv.p == nullptr) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2 * NU; ++i) {
       int idx = threadIdx.x + i * 256;
       int row = idx >> 4, col = idx & 15;
       *reinterpret_cast<u32x4*>(q_lds + row * kQRow + col * 16) =
-          *reinterpret_cast<const u32x4*>(q + (int64_t)(b * kTQ + row) * d + h * kHD + col * 8);
+          *reinterpret_cast<const u32x4*>(q + (int64_t)(b * kTQ + q0 + row) * d + h * kHD + col * 8);
     }
   } else {
+    // thread (row = t/4, seg = t%4): features [16 seg, +16) and their rotary partners of one row.  K / V rows: tree
+    // node `row` (all 64, by all threads); Q rows: query q0 + row (the first 32 NU rows of threads).
     const int row = threadIdx.x >> 2, seg = threadIdx.x & 3;
-    const int64_t grow = (int64_t)b * kTQ + row;
-    const float* cs_row = cs + grow * kHD;  // 64 pairs x 2
-    uint8_t* qrow = q_lds + row * kQRow;
+    const int64_t grow_kv = (int64_t)b * kTQ + row, grow_q = (int64_t)b * kTQ + q0 + row;
+    const float* cs_kv = cs + grow_kv * kHD;  // 64 pairs x 2
     auto stage_q = [&](float (&lo)[16], float (&hi)[16]) {
-      rope16(cs_row, seg, lo, hi);
+      uint8_t* qrow = q_lds + row * kQRow;
+      rope16(cs + grow_q * kHD, seg, lo, hi);
       *reinterpret_cast<u32x4*>(qrow + 32 * seg) = pack8<E>(lo);
       *reinterpret_cast<u32x4*>(qrow + 32 * seg + 16) = pack8<E>(lo + 8);
       *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg) = pack8<E>(hi);
       *reinterpret_cast<u32x4*>(qrow + 128 + 32 * seg + 16) = pack8<E>(hi + 8);
     };
-    if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
-      // (the query heads of one group all produce their shared key/value rows: identical values, no ordering needed)
-      float lo[3][16], hi[3][16];
-      const int cols[3] = {h * kHD, d + hk * kHD, d + dkv + hk * kHD};  // columns of q, k, v in the QKV output
-      qkv_gather<3>(qkv, grow, cols, seg, lo, hi);
-      stage_q(lo[0], hi[0]);
+    // rotates the key row and writes the node's K and V rows into the cache
+    auto write_kv = [&](float (&klo)[16], float (&khi)[16], float (&vlo)[16], float (&vhi)[16]) {
       const int slot = S + row;
-      rope16(cs_row, seg, lo[1], hi[1]);
+      rope16(cs_kv, seg, klo, khi);
       if constexpr (Q8) {
         // row scales: the largest magnitude over the 4 threads (seg) of the row, then codes of this thread's 2 x 16 features
         float am[2] = {0.f, 0.f};
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) am[m] = fmaxf(am[m], fmaxf(fabsf(lo[1 + m][i]), fabsf(hi[1 + m][i])));
+          for (int i = 0; i < 16; ++i) am[m] = fmaxf(am[m], fmaxf(fabsf((m == 0 ? klo : vlo)[i]), fabsf((m == 0 ? khi : vhi)[i])));
           am[m] = fmaxf(am[m], __shfl_xor(am[m], 1, 64));
           am[m] = fmaxf(am[m], __shfl_xor(am[m], 2, 64));
         }
@@ -177,8 +181,8 @@ __global__ void __launch_bounds__(256)
         // 8 consecutive features of one key are 8 contiguous bytes of the 8-bit K layout
 #pragma unroll
         for (int gh2 = 0; gh2 < 2; ++gh2) {
-          const float* a = lo[1] + 8 * gh2;
-          const float* c = hi[1] + 8 * gh2;
+          const float* a = klo + 8 * gh2;
+          const float* c = khi + 8 * gh2;
           *reinterpret_cast<uint2*>(k8 + kv8_k_code(slot, 16 * seg + 8 * gh2)) =
               uint2{kv8_pack4(a[0], a[1], a[2], a[3], ks), kv8_pack4(a[4], a[5], a[6], a[7], ks)};
           *reinterpret_cast<uint2*>(k8 + kv8_k_code(slot, 64 + 16 * seg + 8 * gh2)) =
@@ -186,8 +190,8 @@ __global__ void __launch_bounds__(256)
         }
 #pragma unroll
         for (int i = 0; i < 16; i += 4) {
-          const uint32_t wl = kv8_pack4(lo[2][i], lo[2][i + 1], lo[2][i + 2], lo[2][i + 3], vs);
-          const uint32_t wh = kv8_pack4(hi[2][i], hi[2][i + 1], hi[2][i + 2], hi[2][i + 3], vs);
+          const uint32_t wl = kv8_pack4(vlo[i], vlo[i + 1], vlo[i + 2], vlo[i + 3], vs);
+          const uint32_t wh = kv8_pack4(vhi[i], vhi[i + 1], vhi[i + 2], vhi[i + 3], vs);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v8[kv8_v_code(slot, 16 * seg + i + e)] = (uint8_t)(wl >> (8 * e));
@@ -200,27 +204,50 @@ __global__ void __launch_bounds__(256)
         }
       } else {
         // 8 consecutive features of one key are 16 contiguous bytes of the tiled K layout
-        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack8<E>(lo[1]);
-        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack8<E>(lo[1] + 8);
-        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack8<E>(hi[1]);
-        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack8<E>(hi[1] + 8);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg)) = pack8<E>(klo);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 16 * seg + 8)) = pack8<E>(klo + 8);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg)) = pack8<E>(khi);
+        *reinterpret_cast<u32x4*>(kc + k_index(g, layer, b, hk, slot, 64 + 16 * seg + 8)) = pack8<E>(khi + 8);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = from_float<E>(lo[2][i]);
-          vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = from_float<E>(hi[2][i]);
+          vc[v_index(g, layer, b, hk, slot, 16 * seg + i)] = from_float<E>(vlo[i]);
+          vc[v_index(g, layer, b, hk, slot, 64 + 16 * seg + i)] = from_float<E>(vhi[i]);
         }
       }
-    } else {
+    };
+    if (blk_end * 32 > S && blk_begin < blk_end) {  // this range reaches the tree slots: produce their K / V rows
+      // (workgroups of one key/value head that reach the tree slots all write them: identical values, no ordering needed)
+      if constexpr (NU == 2) {
+        float lo[3][16], hi[3][16];
+        const int cols[3] = {h * kHD, d + hk * kHD, d + dkv + hk * kHD};  // columns of q, k, v in the QKV output
+        qkv_gather<3>(qkv, grow_kv, cols, seg, lo, hi);
+        stage_q(lo[0], hi[0]);
+        write_kv(lo[1], hi[1], lo[2], hi[2]);
+      } else {
+        float lo[2][16], hi[2][16];
+        const int cols[2] = {d + hk * kHD, d + dkv + hk * kHD};
+        qkv_gather<2>(qkv, grow_kv, cols, seg, lo, hi);
+        write_kv(lo[0], hi[0], lo[1], hi[1]);
+        if (row < kQW) {
+          float ql[1][16], qh[1][16];
+          const int qcols[1] = {h * kHD};
+          qkv_gather<1>(qkv, grow_q, qcols, seg, ql, qh);
+          stage_q(ql[0], qh[0]);
+        }
+      }
+    } else if (row < kQW) {
       float lo[1][16], hi[1][16];
       const int cols[1] = {h * kHD};
-      qkv_gather<1>(qkv, grow, cols, seg, lo, hi);
+      qkv_gather<1>(qkv, grow_q, cols, seg, lo, hi);
       stage_q(lo[0], hi[0]);
     }
   }
   __syncthreads();  // Q tile complete; the tree rows written above are complete (stores drain before a barrier)
   // B operand of scores^T: lane holds query 32u + qi, features 16ks + 8gh .. +7
   const uint8_t* qfrag = q_lds + qi * kQRow + gh * 16;
-  const uint64_t mq[2] = {t.anc_mask[qi], t.anc_mask[32 + qi]};
+  uint64_t mq[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) mq[u] = t.anc_mask[q0 + 32 * u + qi];
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
 
   // 16-bit rows: block blk, unit i at kp[blk*512 + i*64].  8-bit rows: a block is 264 16-byte pieces: unit i at
@@ -242,12 +269,14 @@ __global__ void __launch_bounds__(256)
     vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
   }
 
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  f32x16 o[4][2];
+  float m_run[NU], l_run[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) m_run[u] = -INFINITY, l_run[u] = 0.f;
+  f32x16 o[4][NU];
 #pragma unroll
   for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < NU; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[tt][u][r] = 0.f;
 
@@ -268,16 +297,16 @@ __global__ void __launch_bounds__(256)
     // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
     // than in 64 registers per lane that this kernel does not have to spare.
     asm volatile("" ::: "memory");
-    f32x16 sc[2];
+    f32x16 sc[NU];
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < NU; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[u][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const u32x4 ka = Q8 ? fp8x8_to_elem<E>(kd[ks >> 1], ks & 1) : kd[ks];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < NU; ++u) {
         const u32x4 qv = *reinterpret_cast<const u32x4*>(qfrag + u * 32 * kQRow + ks * 32);
         sc[u] = Elem16<E>::mfma(ka, qv, sc[u]);
       }
@@ -287,10 +316,10 @@ __global__ void __launch_bounds__(256)
     // tree are not.  rel0 (wave-uniform) = offset of the block's first key from the tree's first slot.
     const int rel0 = blk * 32 - S;
     const bool need_mask = rel0 + 32 > 0;  // wave-uniform: the block reaches past the prefix
-    float alpha[2];
-    u32x4 pf[2][2];
+    float alpha[NU];
+    u32x4 pf[NU][2];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < NU; ++u) {
       float bmax = -INFINITY;
       // register r is key 8*(r/4) + 4*gh + r%4 of the block; its scale is component r%4 of scale piece r/4
       if (need_mask) {  // wave-uniform branch: only the (at most three) blocks that hold tree slots pay for the mask
@@ -334,11 +363,11 @@ __global__ void __launch_bounds__(256)
       pf[u][0] = u32x4{pk[0], pk[1], pk[2], pk[3]};
       pf[u][1] = u32x4{pk[4], pk[5], pk[6], pk[7]};
     }
-    if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) {
+    if (__any(alpha[0] != 1.f || alpha[NU - 1] != 1.f)) {
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < NU; ++u)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[tt][u][r] *= alpha[u];
     }
@@ -348,7 +377,7 @@ __global__ void __launch_bounds__(256)
       for (int s2 = 0; s2 < 2; ++s2) {
         const u32x4 va = Q8 ? fp8x8_to_elem<E>(vd[tt], s2) : vd[tt * 2 + s2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) o[tt][u] = Elem16<E>::mfma(va, pf[u][s2], o[tt][u]);
+        for (int u = 0; u < NU; ++u) o[tt][u] = Elem16<E>::mfma(va, pf[u][s2], o[tt][u]);
       }
   };
 
@@ -372,31 +401,32 @@ __global__ void __launch_bounds__(256)
 
   // ---- merge the four waves through LDS (fixed order) ------------------------------------------
   __syncthreads();  // every wave is done reading the Q tile that the merge buffer overlays
-  float* o_lds = lds;                             // [4][kHD][kOPad]
-  float* m_lds = lds + 4 * kHD * kOPad;           // [4][kTQ]
-  float* l_lds = m_lds + 4 * kTQ;                 // [4][kTQ]
+  float* o_lds = lds;                             // [4][kHD][kOPadN]
+  float* m_lds = lds + 4 * kHD * kOPadN;          // [4][kQW]
+  float* l_lds = m_lds + 4 * kQW;                 // [4][kQW]
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
+  for (int u = 0; u < NU; ++u) {
     float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
     if (gh == 0) {
-      m_lds[wave * kTQ + 32 * u + qi] = m_run[u];
-      l_lds[wave * kTQ + 32 * u + qi] = l_tot;
+      m_lds[wave * kQW + 32 * u + qi] = m_run[u];
+      l_lds[wave * kQW + 32 * u + qi] = l_tot;
     }
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         int hd = 32 * tt + 8 * (r >> 2) + 4 * gh + (r & 3);
-        o_lds[(wave * kHD + hd) * kOPad + 32 * u + qi] = o[tt][u][r];
+        o_lds[(wave * kHD + hd) * kOPadN + 32 * u + qi] = o[tt][u][r];
       }
   }
   __syncthreads();
-  // thread (qq = t/4, s = t%4) merges features 16*jj + 4*s + e (jj < 8, e < 4) of query qq
-  const int qq = threadIdx.x >> 2, s4 = (threadIdx.x & 3) * 4;
+  // kTPQ threads per query; thread (qq = t / kTPQ, s = t % kTPQ) merges features 16*jj + kEW*s + e (jj < 8, e < kEW)
+  constexpr int kTPQ = 256 / kQW, kEW = 16 / kTPQ;
+  const int qq = threadIdx.x / kTPQ, s4 = (threadIdx.x % kTPQ) * kEW;
   float mw[4], M = -INFINITY;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
-    mw[w] = m_lds[w * kTQ + qq];
+    mw[w] = m_lds[w * kQW + qq];
     M = fmaxf(M, mw[w]);
   }
   const float M_safe = M == -INFINITY ? 0.f : M;
@@ -404,33 +434,42 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
     wt[w] = fast_exp2(mw[w] - M_safe);
-    L += wt[w] * l_lds[w * kTQ + qq];
+    L += wt[w] * l_lds[w * kQW + qq];
   }
-  float acc[32];
+  float acc[8 * kEW];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    const int f = 16 * (j >> 2) + s4 + (j & 3);
+  for (int j = 0; j < 8 * kEW; ++j) {
+    const int f = 16 * (j / kEW) + s4 + (j % kEW);
     float a = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) a += wt[w] * o_lds[(w * kHD + f) * kOPad + qq];
+    for (int w = 0; w < 4; ++w) a += wt[w] * o_lds[(w * kHD + f) * kOPadN + qq];
     acc[j] = a;
   }
+  const int q_out = q0 + qq;  // the query's row among the 64 of its sequence
   if (n_splits == 1) {
     const float inv = 1.0f / L;
-    E* dst = att_out + (int64_t)(b * kTQ + qq) * d + h * kHD + s4;
+    E* dst = att_out + (int64_t)(b * kTQ + q_out) * d + h * kHD + s4;
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj)
-      *reinterpret_cast<uint2*>(dst + 16 * jj) = uint2{Elem16<E>::pack2(acc[4 * jj] * inv, acc[4 * jj + 1] * inv),
-                                                       Elem16<E>::pack2(acc[4 * jj + 2] * inv, acc[4 * jj + 3] * inv)};
+    for (int jj = 0; jj < 8; ++jj) {
+      if constexpr (kEW == 4)
+        *reinterpret_cast<uint2*>(dst + 16 * jj) = uint2{Elem16<E>::pack2(acc[4 * jj] * inv, acc[4 * jj + 1] * inv),
+                                                         Elem16<E>::pack2(acc[4 * jj + 2] * inv, acc[4 * jj + 3] * inv)};
+      else
+        *reinterpret_cast<uint32_t*>(dst + 16 * jj) = Elem16<E>::pack2(acc[2 * jj] * inv, acc[2 * jj + 1] * inv);
+    }
   } else {
     const int64_t pidx = ((int64_t)(b * q_heads(g) + h) * n_splits + split);
-    float* po = part_o + (pidx * kTQ + qq) * kHD + s4;
+    float* po = part_o + (pidx * kTQ + q_out) * kHD + s4;
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj)
-      *reinterpret_cast<float4*>(po + 16 * jj) = float4{acc[4 * jj], acc[4 * jj + 1], acc[4 * jj + 2], acc[4 * jj + 3]};
-    if ((threadIdx.x & 3) == 0) {
-      part_ml[(pidx * 2 + 0) * kTQ + qq] = M;
-      part_ml[(pidx * 2 + 1) * kTQ + qq] = L;
+    for (int jj = 0; jj < 8; ++jj) {
+      if constexpr (kEW == 4)
+        *reinterpret_cast<float4*>(po + 16 * jj) = float4{acc[4 * jj], acc[4 * jj + 1], acc[4 * jj + 2], acc[4 * jj + 3]};
+      else
+        *reinterpret_cast<float2*>(po + 16 * jj) = float2{acc[2 * jj], acc[2 * jj + 1]};
+    }
+    if (threadIdx.x % kTPQ == 0) {
+      part_ml[(pidx * 2 + 0) * kTQ + q_out] = M;
+      part_ml[(pidx * 2 + 1) * kTQ + q_out] = L;
     }
   }
 }
@@ -501,16 +540,19 @@ int64_t attn_mfma_scratch_bytes(int B, int n_heads, int max_prefix) {
   return s == 1 ? 0 : (int64_t)B * n_heads * s * (kTQ * kHD + 2 * kTQ) * 4;
 }
 
-template <typename E, bool Q8>
+template <typename E, bool Q8, int NU>
 static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
                                    void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                                    void* scratch, int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
+  // the merge buffer [4][128][32 NU + 2] + [4][2][32 NU] floats overlays the staged Q tile
+  constexpr int lds_bytes = 4 * kHD * (32 * NU + 2) * 4 + 4 * 2 * 32 * NU * 4;
+  static_assert(lds_bytes >= 32 * NU * kQRow && lds_bytes * (3 - NU) <= 160 * 1024, "LDS budget of the tree kernel");
   static bool attr_set = false;
   if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E, Q8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes));
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E, Q8, NU>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const int nq = q_heads(g);
@@ -519,9 +561,9 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
               "attention: scratch too small");
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (int64_t)B * nq * splits * kTQ * kHD;
-  dim3 grid(splits, nq, B);
+  dim3 grid(splits, nq, B * (3 - NU));  // NU = 1: blockIdx.z = 2 * sequence + half
   const Partials none = single_slot(nullptr, 0, 0);
-  attn_tree_mfma_kernel<E, Q8><<<grid, 256, kAttnLdsBytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
+  attn_tree_mfma_kernel<E, Q8, NU><<<grid, 256, lds_bytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
                                                              layer, seq_len, max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
@@ -534,11 +576,21 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
 int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g,
                           void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                           void* scratch, int64_t scratch_bytes, hipStream_t st) {
-  if (g.quant)
-    MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, true>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
-                                                                    att_out, scratch, scratch_bytes, st)));
-  MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, false>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix,
-                                                                   att_out, scratch, scratch_bytes, st)));
+  // 32 queries per workgroup (two workgroups per CU) where the kernel's time is its fixed chain and the machine has
+  // room for twice the workgroups; 64 where K and V are long enough that passing them through the CUs twice costs
+  // more (measured crossover: between 3K and 4K keys for 16-bit rows, between 4K and 16K for 8-bit rows).
+  static const char* env = getenv("MDZ_ATTN_HALVES");  // development knob: 1 = 32 queries per workgroup, 0 = 64
+  const bool halves = env ? atoi(env) != 0 : (B * q_heads(g) <= 256 && max_prefix < (g.quant ? 6144 : 3584));
+#define MDZ_ATTN_CASE(Q8, NU)                                                                                          \
+  MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, Q8, NU>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B,    \
+                                                                    max_prefix, att_out, scratch, scratch_bytes, st)))
+  if (g.quant) {
+    if (halves) MDZ_ATTN_CASE(true, 1);
+    MDZ_ATTN_CASE(true, 2);
+  }
+  if (halves) MDZ_ATTN_CASE(false, 1);
+  MDZ_ATTN_CASE(false, 2);
+#undef MDZ_ATTN_CASE
 }
 
 }  // namespace mdz
