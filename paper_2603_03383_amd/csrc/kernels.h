@@ -69,16 +69,16 @@ int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStre
 
 // ---- selection kernels (select.hip) -----------------------------------------------------------------
 // out[r] = argmax_v logits[r][v], ties -> lowest v
-// (scratch: topk_scratch_bytes(rows, k) bytes enable the two-stage kernels for long rows; may be NULL)
+// (scratch: topk_scratch_bytes(rows) bytes enable the two-stage kernels for long rows; may be NULL)
 int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,
                   hipStream_t st);
-int64_t topk_scratch_bytes(int rows, int k);
+int64_t topk_scratch_bytes(int rows);
 // out[r][0..k) = indices of the k largest of logits[r][:], descending, ties -> lower index
 int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld, void* scratch,
                 int64_t scratch_bytes, hipStream_t st);
 // Candidate selection of all heads at once from logits [B][K+1][V] (row 0 of a sequence: the base LM head, used
 // only when root_token is NULL): fills cand_flat [B][n_cand].  Needs heads_select_supported().
-bool heads_select_supported(int tree, int B, int V, int64_t scratch_bytes);
+bool heads_select_supported(int tree, int B, int V, const void* scratch, int64_t scratch_bytes);
 int launch_heads_select(int tree, const float* logits, int B, int V, const int32_t* root_token, int32_t* cand_flat,
                         void* scratch, hipStream_t st);
 // dst[i * dst_stride] = src[i]

@@ -152,7 +152,10 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.h = take((int64_t)B * m.d * es);
   w.z = take((int64_t)B * m.d * es);
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
-  w.sel_bytes = topk_scratch_bytes((int)rows > B ? (int)rows : B, 16);
+  {  // candidate lists of the selection kernels: the verify step's rows, or the heads' B * (K + 1) rows
+    const int64_t head_rows = (int64_t)B * (t->K + 1);
+    w.sel_bytes = topk_scratch_bytes((int)(rows > head_rows ? rows : head_rows));
+  }
   w.sel = take(w.sel_bytes);
   KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (is_16bit(m.dtype) && m.head_dim % 32 == 0) ? 1 : 0,
            m.n_heads / kv_heads(m), 0};
@@ -401,7 +404,7 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   float* hl = head_logits_opt ? head_logits_opt : (float*)(wsb + L.hlogits);
   if ((rc = launch_gather_rows(m.dtype, hidden, src_row, B, Tsrc, m.d, h, st))) return rc;
   // the heads' candidates are selected in one pair of launches after the last GEMM where the shape allows it
-  const bool batched = heads_select_supported(m.tree, B, m.vocab, L.sel_bytes);
+  const bool batched = heads_select_supported(m.tree, B, m.vocab, wsb + L.sel, L.sel_bytes);
   // slot 0: root token
   if (root_token) {
     if (!batched && (rc = launch_scatter_i32(root_token, cand_flat, B, t->n_cand, st))) return rc;

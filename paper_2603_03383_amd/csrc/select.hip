@@ -14,17 +14,30 @@ struct Best {
 // a precedes b in (value descending, index ascending) order
 __device__ inline bool precedes(float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); }
 
+// Best of the wave's 64 candidates, in every lane.  Within a row of 16 lanes the exchange runs on data-parallel
+// primitives (lane ^ 1, lane ^ 2 by quad permutation, then the mirrored lane of the half row and of the row: four
+// steps after which a row agrees); the four row results are read as scalars and combined.  (Twelve LDS-crossbar
+// permutes per call, as __shfl_xor compiles to, made the k sequential picks of a top-k cost microseconds.)
 __device__ inline Best wave_best(Best a) {
+  auto take = [&](float ov, int oi) {
+    if (precedes(ov, oi, a.v, a.i)) a.v = ov, a.i = oi;
+  };
+#define MDZ_DPP_STEP(CTRL)                                                                                      \
+  take(__int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(a.v), CTRL, 0xF, 0xF, false)),             \
+       __builtin_amdgcn_update_dpp(0, a.i, CTRL, 0xF, 0xF, false))
+  MDZ_DPP_STEP(0xB1);   // quad_perm [1,0,3,2]
+  MDZ_DPP_STEP(0x4E);   // quad_perm [2,3,0,1]
+  MDZ_DPP_STEP(0x141);  // row_half_mirror
+  MDZ_DPP_STEP(0x140);  // row_mirror
+#undef MDZ_DPP_STEP
+  Best r{__int_as_float(__builtin_amdgcn_readlane(__float_as_int(a.v), 0)), __builtin_amdgcn_readlane(a.i, 0)};
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(a.v, o, 64);
-    int oi = __shfl_xor(a.i, o, 64);
-    if (precedes(ov, oi, a.v, a.i)) {
-      a.v = ov;
-      a.i = oi;
-    }
+  for (int row = 1; row < 4; ++row) {
+    const float ov = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a.v), 16 * row));
+    const int oi = __builtin_amdgcn_readlane(a.i, 16 * row);
+    if (precedes(ov, oi, r.v, r.i)) r = Best{ov, oi};
   }
-  return a;
+  return r;
 }
 
 // blockDim.x == 256; result valid in every thread
@@ -66,199 +79,158 @@ __global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ log
   }
 }
 
-// ---- two-stage variant for long rows: stage 1 finds the top-k of each of n_chunks column chunks (elements
-// held in registers; n_chunks = 64, or more for rows longer than 131072), stage 2 merges the n_chunks*k candidates.  The top-k of the union of per-chunk top-k
-// lists is the global top-k, and the order is total, so the result equals the single-stage kernel's.
-constexpr int kSelChunks = 64;      // chunks per row, at least
-constexpr int kSelMaxChunks = 256;  // and at most: rows of up to 524288 columns
-constexpr int kSelPerThread = 8;    // stage 1 covers chunks of up to 256*8 = 2048 columns
-static int sel_chunks(int V) {
-  const int need = (V + 256 * kSelPerThread - 1) / (256 * kSelPerThread);
-  return need > kSelChunks ? need : kSelChunks;
+// ---- two-stage variant for long rows ----------------------------------------------------------------------------
+// Stage 1: every wave takes one chunk of 512 columns (8 per lane, in registers) and extracts its top-k, in order, with
+// wave-level exchanges alone (no LDS, no barriers).  Stage 2: one wave per row merges the chunk lists (see below).
+// The top-k of a union of top-k lists is the global top-k and the order is total (value descending, index
+// ascending), so the result equals the single-stage kernel's.
+// Rows come in two flavours: uniform (every row the same k, picks to out + row * out_ld) and heads (row (b, j) of
+// logits [B][K+1][V]: j = 0 the base LM head, whose argmax is the root candidate unless the caller gave root
+// tokens, j = 1..K Medusa head j with its own k = caps[j-1]; picks go straight to the row's segment of
+// cand_flat [B][n_cand] = [root | head 1 | .. | head K]: one pair of launches for all heads of all sequences).
+constexpr int kSelWaveCols = 512;   // columns per stage-1 chunk
+constexpr int kSelMaxChunks = 512;  // rows of up to 262144 columns
+constexpr int kSelMaxK = 16;        // candidates per chunk list (the lists are laid out for this many)
+static int sel_chunks(int V) { return (V + kSelWaveCols - 1) / kSelWaveCols; }
+
+struct SelRows {
+  int tree;        // >= 0: heads flavour over this tree; -1: uniform
+  int k;           // uniform: picks per row
+  int64_t ld;      // uniform: row stride of the logits (heads: V)
+  int64_t out_ld;  // uniform: row stride of the output
+  bool have_root;  // heads: the caller supplies the root candidates
+};
+__device__ inline int sel_row_k(const SelRows& rs, int row) {
+  if (rs.tree < 0) return rs.k;
+  const TreeTables& t = c_trees[rs.tree];
+  const int j = row % (t.K + 1);
+  return j == 0 ? (rs.have_root ? 0 : 1) : t.caps[j - 1];
 }
 
-__global__ void __launch_bounds__(256) topk_stage1_kernel(const float* __restrict__ logits, int V, int64_t ld, int k,
+__global__ void __launch_bounds__(256) topk_stage1_kernel(SelRows rs, const float* __restrict__ logits, int V, int n_chunks,
                                                           float* __restrict__ cand_v, int32_t* __restrict__ cand_i) {
-  __shared__ Best red[4];
-  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
-  const int per = (V + n_chunks - 1) / n_chunks;
-  const int c0 = chunk * per, c1 = min(c0 + per, V);
-  const float* src = logits + (int64_t)row * ld;
-  float v[kSelPerThread];
+  const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), row = blockIdx.y;
+  const int k = sel_row_k(rs, row);
+  if (chunk >= n_chunks || k == 0) return;
+  const int c0 = chunk * kSelWaveCols;
+  const float* src = logits + (int64_t)row * (rs.tree < 0 ? rs.ld : (int64_t)V);
+  float v[8];
 #pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
-    int i = c0 + threadIdx.x + j * 256;
-    v[j] = i < c1 ? src[i] : -INFINITY;
+  for (int j = 0; j < 8; ++j) {
+    const int i = c0 + lane + j * 64;
+    v[j] = i < V ? src[i] : -INFINITY;
   }
+  const int64_t o = ((int64_t)row * n_chunks + chunk) * kSelMaxK;
   float pv = INFINITY;
   int pi = -1;
   for (int p = 0; p < k; ++p) {
     Best b{-INFINITY, kNoIndex};
 #pragma unroll
-    for (int j = 0; j < kSelPerThread; ++j) {
-      int i = c0 + threadIdx.x + j * 256;
-      bool ok = i < c1 && (p == 0 || precedes(pv, pi, v[j], i));
-      if (ok && precedes(v[j], i, b.v, b.i)) {
-        b.v = v[j];
-        b.i = i;
-      }
+    for (int j = 0; j < 8; ++j) {
+      const int i = c0 + lane + j * 64;
+      const bool ok = i < V && (p == 0 || precedes(pv, pi, v[j], i));
+      if (ok && precedes(v[j], i, b.v, b.i)) b = Best{v[j], i};
     }
-    b = block_best_256(b, red);
-    if (threadIdx.x == 0) {
-      int64_t o = ((int64_t)row * n_chunks + chunk) * k + p;
-      cand_v[o] = b.v;
-      cand_i[o] = b.i;
-    }
+    b = wave_best(b);
+    if (lane == 0) cand_v[o + p] = b.v, cand_i[o + p] = b.i;
     pv = b.v;
     pi = b.i;
   }
 }
 
-__global__ void __launch_bounds__(256) topk_stage2_kernel(const float* __restrict__ cand_v,
-                                                          const int32_t* __restrict__ cand_i, int k, int n_chunks,
-                                                          int32_t* __restrict__ out, int64_t out_ld) {
-  __shared__ Best red[4];
-  const int row = blockIdx.x;
-  const int n = n_chunks * k;
-  const float* cv = cand_v + (int64_t)row * n;
-  const int32_t* ci = cand_i + (int64_t)row * n;
-  float pv = INFINITY;
-  int pi = -1;
+// One wave per row.  Every chunk list is already in order, so the row's next pick is the best of the lists' current
+// heads: the lists are staged in LDS, every lane owns up to 8 of them (512 lists at most), offers the best of its
+// heads, the wave picks, and the lane that owned the pick advances that list.
+__global__ void __launch_bounds__(64) topk_stage2_kernel(SelRows rs, const float* __restrict__ cand_v,
+                                                         const int32_t* __restrict__ cand_i, int n_chunks,
+                                                         const int32_t* __restrict__ root_token, int32_t* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(8))) uint8_t sel_lds[];  // [n_chunks][k] values, then indices
+  const int lane = threadIdx.x, row = blockIdx.x;
+  const int k = sel_row_k(rs, row);
+  int32_t* dst;
+  if (rs.tree < 0) {
+    dst = out + (int64_t)row * rs.out_ld;
+  } else {
+    const TreeTables& t = c_trees[rs.tree];
+    const int b = row / (t.K + 1), j = row % (t.K + 1);
+    int seg = 0;  // start of row j's segment in the flat candidate buffer
+    for (int i = 1; i <= j; ++i) seg += i == 1 ? 1 : t.caps[i - 2];
+    dst = out + (int64_t)b * t.n_cand + seg;
+    if (k == 0) {
+      if (lane == 0) dst[0] = root_token[b];
+      return;
+    }
+  }
+  float* lv = reinterpret_cast<float*>(sel_lds);
+  int* li = reinterpret_cast<int*>(sel_lds) + n_chunks * k;
+  const float* cv = cand_v + (int64_t)row * n_chunks * kSelMaxK;
+  const int32_t* ci = cand_i + (int64_t)row * n_chunks * kSelMaxK;
+  for (int c = lane; c < n_chunks; c += 64)
+    for (int q = 0; q < k; ++q) lv[c * k + q] = cv[c * kSelMaxK + q], li[c * k + q] = ci[c * kSelMaxK + q];
+  __syncthreads();
+  int pos[kSelMaxChunks / 64];  // next entry of the lane's lists lane, lane + 64, ...
+#pragma unroll
+  for (int j = 0; j < kSelMaxChunks / 64; ++j) pos[j] = 0;
   for (int p = 0; p < k; ++p) {
     Best b{-INFINITY, kNoIndex};
-    for (int j = threadIdx.x; j < n; j += 256) {
-      float v = cv[j];
-      int i = ci[j];
-      bool ok = i != kNoIndex && (p == 0 || precedes(pv, pi, v, i));
-      if (ok && precedes(v, i, b.v, b.i)) {
-        b.v = v;
-        b.i = i;
+#pragma unroll
+    for (int j = 0; j < kSelMaxChunks / 64; ++j) {
+      const int c = lane + 64 * j;
+      if (c < n_chunks && pos[j] < k) {
+        const Best h{lv[c * k + pos[j]], li[c * k + pos[j]]};
+        if (h.i != kNoIndex && precedes(h.v, h.i, b.v, b.i)) b = h;
       }
     }
-    b = block_best_256(b, red);
-    if (threadIdx.x == 0) out[(int64_t)row * out_ld + p] = b.i == kNoIndex ? -1 : b.i;
-    pv = b.v;
-    pi = b.i;
+    const Best w = wave_best(b);
+    if (lane == 0) dst[p] = w.i == kNoIndex ? -1 : w.i;
+    if (w.i != kNoIndex && w.i == b.i) {  // column ids are unique: this lane owns the pick; advance its list
+#pragma unroll
+      for (int j = 0; j < kSelMaxChunks / 64; ++j) {
+        const int c = lane + 64 * j;
+        if (c < n_chunks && pos[j] < k && li[c * k + pos[j]] == w.i) ++pos[j];
+      }
+    }
   }
 }
 
-// (sized for the largest chunk count, so it does not depend on the row length)
-int64_t topk_scratch_bytes(int rows, int k) { return (int64_t)rows * kSelMaxChunks * k * 8; }
+// bytes of candidate lists for `rows` rows (sized for the largest chunk count, so independent of the row length)
+int64_t topk_scratch_bytes(int rows) { return (int64_t)rows * kSelMaxChunks * kSelMaxK * 8; }
+
+static bool two_stage_ok(int rows, int V, int k, const void* scratch, int64_t scratch_bytes) {
+  return V >= 8192 && sel_chunks(V) <= kSelMaxChunks && k <= kSelMaxK && scratch &&
+         scratch_bytes >= (int64_t)rows * sel_chunks(V) * kSelMaxK * 8;
+}
+
+static int launch_two_stage(const SelRows& rs, const float* logits, int rows, int V, const int32_t* root_token,
+                            int32_t* out, void* scratch, hipStream_t st) {
+  const int n_chunks = sel_chunks(V);
+  float* cv = (float*)scratch;
+  int32_t* ci = (int32_t*)(cv + (int64_t)rows * n_chunks * kSelMaxK);
+  topk_stage1_kernel<<<dim3((n_chunks + 3) / 4, rows), 256, 0, st>>>(rs, logits, V, n_chunks, cv, ci);
+  MDZ_LAUNCH_CHECK();
+  const int kmax = rs.tree < 0 ? rs.k : kSelMaxK;
+  topk_stage2_kernel<<<rows, 64, (size_t)n_chunks * kmax * 8, st>>>(rs, cv, ci, n_chunks, root_token, out);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
 
 int launch_topk(const float* logits, int rows, int V, int64_t ld, int k, int32_t* out, int64_t out_ld, void* scratch,
                 int64_t scratch_bytes, hipStream_t st) {
   ProfScope prof_(PROF_SELECT, st);
   if (rows == 0 || k == 0) return MDZ_OK;
-  const int n_chunks = sel_chunks(V);
-  if (V >= 8192 && n_chunks <= kSelMaxChunks && scratch && scratch_bytes >= topk_scratch_bytes(rows, k)) {
-    float* cv = (float*)scratch;
-    int32_t* ci = (int32_t*)(cv + (int64_t)rows * n_chunks * k);
-    topk_stage1_kernel<<<dim3(n_chunks, rows), 256, 0, st>>>(logits, V, ld, k, cv, ci);
-    MDZ_LAUNCH_CHECK();
-    topk_stage2_kernel<<<rows, 256, 0, st>>>(cv, ci, k, n_chunks, out, out_ld);
-  } else {
-    topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
-  }
+  if (two_stage_ok(rows, V, k, scratch, scratch_bytes))
+    return launch_two_stage(SelRows{-1, k, ld, out_ld, false}, logits, rows, V, nullptr, out, scratch, st);
+  topk_kernel<<<rows, 256, 0, st>>>(logits, V, ld, k, out, out_ld);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
 
-// ---- all heads of all sequences in one pair of launches --------------------------------------------------------
-// Row (b, j) of logits [B][K+1][V]: j = 0 is the base LM head (its argmax is the root candidate unless the caller
-// gave root tokens), j = 1..K Medusa head j with its own top-k size caps[j-1].  The picks go straight to their
-// segment of cand_flat [B][n_cand] = [root | head 1 | .. | head K].  Same two stages and the same total order as
-// above, so the result equals per-head launches; it replaces 2 (K + 1) launches of ~10 us each by 2.
-constexpr int kHeadsMaxK = 16;  // largest per-head top-k the stage-1 buffer is laid out for
-__device__ inline int heads_row_k(const TreeTables& t, int j, bool have_root) { return j == 0 ? (have_root ? 0 : 1) : t.caps[j - 1]; }
-
-__global__ void __launch_bounds__(256) heads_topk_stage1_kernel(int tree, const float* __restrict__ logits, int V,
-                                                                bool have_root, float* __restrict__ cand_v,
-                                                                int32_t* __restrict__ cand_i) {
-  __shared__ Best red[4];
-  const TreeTables& t = c_trees[tree];
-  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
-  const int k = heads_row_k(t, row % (t.K + 1), have_root);
-  if (k == 0) return;
-  const int per = (V + n_chunks - 1) / n_chunks;
-  const int c0 = chunk * per, c1 = min(c0 + per, V);
-  const float* src = logits + (int64_t)row * V;
-  float v[kSelPerThread];
-#pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
-    int i = c0 + threadIdx.x + j * 256;
-    v[j] = i < c1 ? src[i] : -INFINITY;
-  }
-  float pv = INFINITY;
-  int pi = -1;
-  for (int p = 0; p < k; ++p) {
-    Best b{-INFINITY, kNoIndex};
-#pragma unroll
-    for (int j = 0; j < kSelPerThread; ++j) {
-      int i = c0 + threadIdx.x + j * 256;
-      bool ok = i < c1 && (p == 0 || precedes(pv, pi, v[j], i));
-      if (ok && precedes(v[j], i, b.v, b.i)) {
-        b.v = v[j];
-        b.i = i;
-      }
-    }
-    b = block_best_256(b, red);
-    if (threadIdx.x == 0) {
-      int64_t o = ((int64_t)row * n_chunks + chunk) * kHeadsMaxK + p;
-      cand_v[o] = b.v;
-      cand_i[o] = b.i;
-    }
-    pv = b.v;
-    pi = b.i;
-  }
-}
-
-__global__ void __launch_bounds__(256) heads_topk_stage2_kernel(int tree, const float* __restrict__ cand_v,
-                                                                const int32_t* __restrict__ cand_i, int n_chunks,
-                                                                const int32_t* __restrict__ root_token,
-                                                                int32_t* __restrict__ cand_flat) {
-  __shared__ Best red[4];
-  const TreeTables& t = c_trees[tree];
-  const int row = blockIdx.x, b = row / (t.K + 1), j = row % (t.K + 1);
-  int seg = 0;  // start of row j's segment in the flat candidate buffer
-  for (int i = 1; i <= j; ++i) seg += i == 1 ? 1 : t.caps[i - 2];
-  int32_t* out = cand_flat + (int64_t)b * t.n_cand + seg;
-  const int k = heads_row_k(t, j, root_token != nullptr);
-  if (k == 0) {
-    if (threadIdx.x == 0) out[0] = root_token[b];
-    return;
-  }
-  const float* cv = cand_v + (int64_t)row * n_chunks * kHeadsMaxK;
-  const int32_t* ci = cand_i + (int64_t)row * n_chunks * kHeadsMaxK;
-  const int n = n_chunks * k;
-  float pv = INFINITY;
-  int pi = -1;
-  for (int p = 0; p < k; ++p) {
-    Best bst{-INFINITY, kNoIndex};
-    for (int e = threadIdx.x; e < n; e += 256) {
-      const int at = (e / k) * kHeadsMaxK + e % k;
-      float v = cv[at];
-      int i = ci[at];
-      bool ok = i != kNoIndex && (p == 0 || precedes(pv, pi, v, i));
-      if (ok && precedes(v, i, bst.v, bst.i)) {
-        bst.v = v;
-        bst.i = i;
-      }
-    }
-    bst = block_best_256(bst, red);
-    if (threadIdx.x == 0) out[p] = bst.i == kNoIndex ? -1 : bst.i;
-    pv = bst.v;
-    pi = bst.i;
-  }
-}
-
 // true if launch_heads_select can serve this shape with this much scratch (else the caller selects head by head)
-bool heads_select_supported(int tree, int B, int V, int64_t scratch_bytes) {
+bool heads_select_supported(int tree, int B, int V, const void* scratch, int64_t scratch_bytes) {
   const TreeTables* t = host_tree(tree);
   int kmax = 1;
   for (int k = 0; k < t->K; ++k) kmax = t->caps[k] > kmax ? t->caps[k] : kmax;
-  const int n_chunks = sel_chunks(V);
-  return V >= 8192 && n_chunks <= kSelMaxChunks && kmax <= kHeadsMaxK &&
-         scratch_bytes >= (int64_t)B * (t->K + 1) * n_chunks * kHeadsMaxK * 8;
+  return two_stage_ok(B * (t->K + 1), V, kmax, scratch, scratch_bytes);
 }
 
 int launch_heads_select(int tree, const float* logits, int B, int V, const int32_t* root_token, int32_t* cand_flat,
@@ -267,14 +239,7 @@ int launch_heads_select(int tree, const float* logits, int B, int V, const int32
   const TreeTables* t = host_tree(tree);
   const int rows = B * (t->K + 1);
   if (rows == 0) return MDZ_OK;
-  const int n_chunks = sel_chunks(V);
-  float* cv = (float*)scratch;
-  int32_t* ci = (int32_t*)(cv + (int64_t)rows * n_chunks * kHeadsMaxK);
-  heads_topk_stage1_kernel<<<dim3(n_chunks, rows), 256, 0, st>>>(tree, logits, V, root_token != nullptr, cv, ci);
-  MDZ_LAUNCH_CHECK();
-  heads_topk_stage2_kernel<<<rows, 256, 0, st>>>(tree, cv, ci, n_chunks, root_token, cand_flat);
-  MDZ_LAUNCH_CHECK();
-  return MDZ_OK;
+  return launch_two_stage(SelRows{tree, 0, 0, 0, root_token != nullptr}, logits, rows, V, root_token, cand_flat, scratch, st);
 }
 
 int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,
