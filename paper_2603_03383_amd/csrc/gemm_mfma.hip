@@ -12,7 +12,8 @@
 //   * Work decomposition is flat and persistent: the (column band, K-stage) units are numbered band-major
 //     and cut into gridDim.x equal contiguous ranges, one per workgroup, so every CU streams the same
 //     number of bytes whatever the matrix shape (a per-CU stream is latency bound at ~50 GB/s, so balance
-//     decides the kernel's duration).  A range that ends inside a band leaves a partial sum; partial sums go
+//     decides the kernel's duration).  The grid is one workgroup per CU, or a little fewer when that makes
+//     the ranges line up with the bands (plan_gemm).  A range that ends inside a band leaves a partial sum; partial sums go
 //     to numbered slots of a workspace and the consumer adds slots 0..count-1 in that fixed order, so the
 //     result is deterministic (no floating-point atomics).
 #include "kernels.h"
@@ -245,6 +246,19 @@ static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
   const int n_stages = K / p.ck;
   const int64_t U = (int64_t)bands * n_stages;
   p.slots = 1;
+  // A grid a little under one workgroup per CU whose equal ranges line up with the column bands (a range is a whole
+  // number of bands, or a band a whole number of ranges) leaves no range that straddles a band: fewer partial-sum
+  // slots for the consumer to add and no flush in mid-stream.
+  if (!p.whole && !env) {
+    for (int gsz = kNumCU; gsz >= kNumCU * 3 / 4; --gsz) {
+      if (U % gsz) continue;
+      const int64_t u = U / gsz;
+      if (n_stages % u == 0 || u % n_stages == 0) {
+        p.grid = gsz;
+        break;
+      }
+    }
+  }
   if (p.whole) {
     if (p.grid > bands) p.grid = bands;
   } else {

@@ -48,9 +48,20 @@ def test_slot_counts_equal_a_walk_over_the_ranges(M, N, K, max_split):
     assert most == plan["max_slots"] <= max_split
 
 
-def test_7b_shapes_keep_every_cu_busy():
-    for (N, K) in [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)]:
-        assert P.medusa_gemm_plan(P.MDZ_BF16, 64, N, K, 12)["grid"] == 256
+def test_7b_shapes_keep_the_cus_busy_and_smaller_grids_are_band_aligned():
+    """One workgroup per CU, or at least three quarters of that when the equal ranges then line up with the bands."""
+    expect = {(12288, 4096): 192, (4096, 4096): 256, (22016, 4096): 256, (4096, 11008): 256, (128000, 4096): 250,
+              (6144, 4096): 192, (25600, 4096): 200, (4096, 12800): 256, (153600, 4096): 240}
+    for (N, K), grid in expect.items():
+        plan = P.medusa_gemm_plan(P.MDZ_BF16, 64, N, K, 12)
+        assert plan["grid"] == grid
+        if grid < 256:
+            units = (N // plan["band_cols"]) * plan["n_stages"]
+            assert units % grid == 0
+            per = units // grid
+            assert plan["n_stages"] % per == 0 or per % plan["n_stages"] == 0
+            writers = brute_force_writers(N, plan["band_cols"], plan["n_stages"], grid)
+            assert len({len(w) for w in writers}) == 1, "every band has the same number of writers"
 
 
 def test_plan_rejects_shapes_the_streaming_kernel_does_not_take():
