@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E peak
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
 # of known size; see profiles/gemm_w64_cfg3_step_1k_pmc.md).  Measured offline; not re-measured by this script.
-TRAFFIC_W64 = {"fetch_bytes_per_launch": 112.50e6, "write_bytes_per_launch": 10.43e6,
+TRAFFIC_W64 = {"fetch_bytes_per_launch": 112.62e6, "write_bytes_per_launch": 9.39e6,
                "source": "profiles/gemm_w64_cfg3_step_1k_pmc.md"}
 
 
