@@ -578,9 +578,9 @@ int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qk
                           void* scratch, int64_t scratch_bytes, hipStream_t st) {
   // 32 queries per workgroup (two workgroups per CU) where the kernel's time is its fixed chain and the machine has
   // room for twice the workgroups; 64 where K and V are long enough that passing them through the CUs twice costs
-  // more (measured crossover: between 3K and 4K keys for 16-bit rows, between 4K and 16K for 8-bit rows).
+  // more (measured crossover: between 3K and 4K keys for 16-bit rows, between 12K and 16K for 8-bit rows).
   static const char* env = getenv("MDZ_ATTN_HALVES");  // development knob: 1 = 32 queries per workgroup, 0 = 64
-  const bool halves = env ? atoi(env) != 0 : (B * q_heads(g) <= 256 && max_prefix < (g.quant ? 6144 : 3584));
+  const bool halves = env ? atoi(env) != 0 : (B * q_heads(g) <= 256 && max_prefix < (g.quant ? 14336 : 3584));
 #define MDZ_ATTN_CASE(Q8, NU)                                                                                          \
   MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, Q8, NU>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B,    \
                                                                     max_prefix, att_out, scratch, scratch_bytes, st)))

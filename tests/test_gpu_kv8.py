@@ -124,9 +124,9 @@ def check_layer_kv8(r, S_list, w, x_seed):
     return err / _scale(r["ref"]), err2 / _scale(ref2), worst_frac
 
 
-# (6200 keys: beyond the prefix up to which a workgroup carries 32 of the 64 queries, so both kernel variants run)
+# (14400 keys: beyond the prefix up to which a workgroup carries 32 of the 64 queries, so both kernel variants run)
 @pytest.mark.parametrize("S_list,max_prefix", [([0], 0), ([77], 100), ([1024], 1024), ([300, 0, 45], 300), ([5000], 5003),
-                                                ([6200], 6200)])
+                                                ([14400], 14400)])
 @pytest.mark.parametrize("kv_heads,dtype", [(0, "bf16"), (8, "bf16"), (8, "fp16")], ids=["mha-bf16", "gqa8-bf16", "gqa8-fp16"])
 def test_7b_width_layer_8bit_rows(S_list, max_prefix, kv_heads, dtype):
     w = W.CONFIGS["cfg2_layer_bf16"].with_(name="layer_kv8", dtype=dtype, n_kv_heads=kv_heads, prefix=tuple(S_list),
