@@ -136,6 +136,48 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
     blk_end = (int)((int64_t)(split + 1) * nb / n_splits);
   }
 
+  // 16-bit rows: block blk, unit i at kp[blk*512 + i*64].  8-bit rows: a block is 264 16-byte pieces: unit i at
+  // kp[blk*264 + i*64], the four scales of keys 8j + 4gh .. +3 at ks_p[blk*264 + 2j]
+  constexpr int kBlkPieces = Q8 ? kKv8BlockBytes / 16 : 512;
+  const u32x4* kp;
+  const u32x4* vp;
+  const u32x4* ks_p = nullptr;
+  const u32x4* vs_p = nullptr;
+  if constexpr (Q8) {
+    const int64_t hb = kv8_head_base(g, layer, b, hk);
+    const u32x4* k0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(kc) + hb);
+    const u32x4* v0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(vc) + hb);
+    kp = k0 + lane, vp = v0 + lane;
+    ks_p = k0 + 256 + gh, vs_p = v0 + 256 + gh;
+  } else {
+    const int64_t head_base = kv_head_base(g, layer, b, hk);
+    kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;
+    vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
+  }
+
+  // K and V are both double buffered one block ahead of the block being multiplied, and every load is
+  // unconditional (past the wave's last block it repeats that block and the result is not used): the wait counters
+  // are in-order, so a wave then keeps a whole block (16 KiB of 16-bit rows) in flight while it works on the
+  // previous one, which is what the HBM latency asks for at one wave per SIMD.
+  u32x4 kb[2][8], vb[2][8];
+  auto load_kv = [&](int blk, u32x4 (&kd)[8], u32x4 (&vd)[8]) {  // 8-bit rows: [0..3] codes, [4..7] the lane's 16 scales
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      kd[i] = (Q8 && i >= 4) ? ks_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : kp[(int64_t)blk * kBlkPieces + i * 64];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      vd[i] = (Q8 && i >= 4) ? vs_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : vp[(int64_t)blk * kBlkPieces + i * 64];
+  };
+  // this wave's blocks: blk_begin + wave, + 4, ... ; two per trip so that the buffers alternate statically
+  const int n_mine = blk_begin + wave < blk_end ? (blk_end - blk_begin - wave + 3) >> 2 : 0;
+  const int first = blk_begin + wave, last = first + 4 * (n_mine - 1);
+  // A first block that lies wholly in the prefix depends on nothing this kernel computes: it is requested before the
+  // prologue below, whose own loads then wait no longer than this one takes.  (A block with tree slots is written
+  // by the prologue first.)
+  // (not for 8-bit rows with 64 queries: that variant has no registers to hold the block through the prologue)
+  const bool preloaded = !(Q8 && NU == 2) && n_mine > 0 && (first + 1) * 32 <= S;
+  if (preloaded) load_kv(first, kb[0], vb[0]);
+
   // Q tile of this head -> LDS (rows padded by 16 B: the 16 B-per-lane operand reads below are bank-conflict
   // free).  The region is reused by the wave merge after the key loop.
   uint8_t* q_lds = reinterpret_cast<uint8_t*>(lds);
@@ -250,25 +292,6 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
   for (int u = 0; u < NU; ++u) mq[u] = t.anc_mask[q0 + 32 * u + qi];
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kHD);
 
-  // 16-bit rows: block blk, unit i at kp[blk*512 + i*64].  8-bit rows: a block is 264 16-byte pieces: unit i at
-  // kp[blk*264 + i*64], the four scales of keys 8j + 4gh .. +3 at ks_p[blk*264 + 2j]
-  constexpr int kBlkPieces = Q8 ? kKv8BlockBytes / 16 : 512;
-  const u32x4* kp;
-  const u32x4* vp;
-  const u32x4* ks_p = nullptr;
-  const u32x4* vs_p = nullptr;
-  if constexpr (Q8) {
-    const int64_t hb = kv8_head_base(g, layer, b, hk);
-    const u32x4* k0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(kc) + hb);
-    const u32x4* v0 = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(vc) + hb);
-    kp = k0 + lane, vp = v0 + lane;
-    ks_p = k0 + 256 + gh, vs_p = v0 + 256 + gh;
-  } else {
-    const int64_t head_base = kv_head_base(g, layer, b, hk);
-    kp = reinterpret_cast<const u32x4*>(kc + head_base) + lane;
-    vp = reinterpret_cast<const u32x4*>(vc + head_base) + lane;
-  }
-
   float m_run[NU], l_run[NU];
 #pragma unroll
   for (int u = 0; u < NU; ++u) m_run[u] = -INFINITY, l_run[u] = 0.f;
@@ -280,19 +303,6 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[tt][u][r] = 0.f;
 
-  // K and V are both double buffered one block ahead of the block being multiplied, and every load is
-  // unconditional (past the wave's last block it repeats that block and the result is not used): the wait counters
-  // are in-order, so a wave then keeps a whole block (16 KiB of 16-bit rows) in flight while it works on the
-  // previous one, which is what the HBM latency asks for at one wave per SIMD.
-  u32x4 kb[2][8], vb[2][8];
-  auto load_kv = [&](int blk, u32x4 (&kd)[8], u32x4 (&vd)[8]) {  // 8-bit rows: [0..3] codes, [4..7] the lane's 16 scales
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      kd[i] = (Q8 && i >= 4) ? ks_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : kp[(int64_t)blk * kBlkPieces + i * 64];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      vd[i] = (Q8 && i >= 4) ? vs_p[(int64_t)blk * kBlkPieces + 2 * (i - 4)] : vp[(int64_t)blk * kBlkPieces + i * 64];
-  };
   auto process = [&](int blk, const u32x4 (&kd)[8], const u32x4 (&vd)[8]) {
     // Compiler barrier: keeps the (loop-invariant) Q operand reads inside the loop, i.e. in LDS rather
     // than in 64 registers per lane that this kernel does not have to spare.
@@ -381,11 +391,8 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
       }
   };
 
-  // this wave's blocks: blk_begin + wave, + 4, ... ; two per trip so that the buffers alternate statically
-  const int n_mine = blk_begin + wave < blk_end ? (blk_end - blk_begin - wave + 3) >> 2 : 0;
   if (n_mine > 0) {
-    const int first = blk_begin + wave, last = first + 4 * (n_mine - 1);
-    load_kv(first, kb[0], vb[0]);
+    if (!preloaded) load_kv(first, kb[0], vb[0]);
     for (int it = 0; it < n_mine; it += 2) {
       const int blk = first + 4 * it;
       load_kv(min(blk + 4, last), kb[1], vb[1]);
