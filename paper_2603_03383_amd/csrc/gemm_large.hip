@@ -11,7 +11,10 @@
 //     so the 16-byte-per-lane A-operand reads are bank-conflict free; every A operand read from LDS feeds two
 //     MFMAs, which keeps the LDS pipe (128 B/clk) below the matrix pipe;
 //   * narrow matrices are split along K into numbered partial-sum slots so that every CU has a tile (the consumer
-//     adds the slots in order: deterministic, no float atomics).
+//     adds the slots in order: deterministic, no float atomics);
+//   * SWIGLU: for the gate/up matrix (gate and up tiles alternate in the packed order, so a wave's two tiles are the
+//     gate and the up columns of the same 32 features) an unsplit launch writes SiLU(gate) * up as E straight from
+//     the accumulators instead of 2 F fp32 sums per row for a second kernel to read back.
 #include "kernels.h"
 
 namespace mdz {
@@ -30,10 +33,13 @@ constexpr int kXL = kBM * (kCK / 8) / 256;  // 16-byte X loads per thread per st
 constexpr int kLdsBytes = 2 * kBM * kLRow;
 }  // namespace
 
-template <typename E>
+__device__ inline float silu_large(float v) { return v / (1.0f + expf(-v)); }
+
+template <typename E, bool SWIGLU>
 __global__ void __launch_bounds__(256)
     gemm_large_kernel(const E* __restrict__ X, int M, int K, const E* __restrict__ Wp, int n_tiles,
-                      float* __restrict__ P, int ldp, int64_t part_stride, int stages_per_split, int nb_n, int nb_m) {
+                      float* __restrict__ P, int ldp, int64_t part_stride, int stages_per_split, int nb_n, int nb_m,
+                      E* __restrict__ U) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
   uint8_t(*lds)[kBM * kLRow] = reinterpret_cast<uint8_t(*)[kBM * kLRow]>(lds_raw);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -148,8 +154,24 @@ __global__ void __launch_bounds__(256)
   }
 
   // D layout of the 32x32 MFMA: lane holds column (lane % 32); register r is row 8*(r/4) + 4*(lane/32) + r%4.
-  float* out = P + (int64_t)blockIdx.z * part_stride;
   const int col = lane & 31, rbase = (lane >> 5) * 4;
+  if constexpr (SWIGLU) {
+    // tiles (2j, 2j + 1) of this wave = gate and up of features 32j .. 32j + 31; U is [M][n_tiles * 16]
+    const int j = bn * 4 + wave;
+    if (2 * j + 1 < n_tiles) {
+      const int F = n_tiles * 16;
+      E* urow = U + j * 32 + col;
+#pragma unroll
+      for (int mt = 0; mt < kBM / 32; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + mt * 32 + 8 * (r >> 2) + rbase + (r & 3);
+          if (m < M) urow[(int64_t)m * F] = from_float<E>(silu_large(acc[0][mt][r]) * acc[1][mt][r]);
+        }
+    }
+    return;
+  }
+  float* out = P + (int64_t)blockIdx.z * part_stride;
   int pitch = ldp;
   asm volatile("" : "+s"(pitch));  // keeps the row offsets out of registers until they are needed
 #pragma unroll
@@ -194,34 +216,46 @@ bool gemm_large_supported(int dtype, int M, int N, int K) {
 // partial-sum slots launch_gemm_large will write for this problem (sizes the slot workspace)
 int gemm_large_slots(int M, int N, int K) { return plan_large(M, N, K).ksplit; }
 
-template <typename E>
+template <typename E, bool SWIGLU>
 static int launch_gemm_large_t(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
-                               int64_t part_stride, Partials* res, hipStream_t st) {
+                               int64_t part_stride, Partials* res, void* U, hipStream_t st) {
   ProfScope prof_(PROF_GEMM_LARGE, st);
   const LargePlan p = plan_large(M, N, K);
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
   static bool attr_set = false;
   if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_large_kernel<E>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes));
+    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_large_kernel<E, SWIGLU>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     attr_set = true;
   }
+  MDZ_REQUIRE(!SWIGLU || (p.ksplit == 1 && N % 64 == 0 && U), MDZ_EUNSUPPORTED, "gemm: fused SwiGLU needs an unsplit launch");
   res->n = p.ksplit;
   res->split_grid = 0;
   res->band_cols = kBN;
   res->n_stages = 1;
   res->split_units = 0;
   const int groups = (p.nb_n + 7) / 8;  // column blocks per XCD
-  gemm_large_kernel<E><<<dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st>>>(
-      (const E*)X, M, K, (const E*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m);
+  gemm_large_kernel<E, SWIGLU><<<dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st>>>(
+      (const E*)X, M, K, (const E*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m, (E*)U);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
 
 int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
                       int64_t part_stride, Partials* res, hipStream_t st) {
-  MDZ_WITH_ELEM16(dtype, return launch_gemm_large_t<E>(X, Wp, P, M, N, K, ldp, part_stride, res, st));
+  MDZ_WITH_ELEM16(dtype, return (launch_gemm_large_t<E, false>(X, Wp, P, M, N, K, ldp, part_stride, res, nullptr, st)));
+}
+
+// gate/up GEMM with the SwiGLU applied in the epilogue: U [M][N / 2] of the storage type.  Only where the large kernel
+// runs unsplit (gemm_large_swiglu_supported); P is not written.
+bool gemm_large_swiglu_supported(int dtype, int M, int N, int K) {
+  return gemm_large_supported(dtype, M, N, K) && N % 64 == 0 && plan_large(M, N, K).ksplit == 1;
+}
+
+int launch_gemm_large_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {
+  Partials unused;
+  MDZ_WITH_ELEM16(dtype, return (launch_gemm_large_t<E, true>(X, Wp, nullptr, M, N, K, N, 0, &unused, U, st)));
 }
 
 }  // namespace mdz

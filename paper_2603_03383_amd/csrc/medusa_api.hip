@@ -33,6 +33,9 @@ int gemm_large_slots(int M, int N, int K);
 int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
                       int64_t part_stride, Partials* res, hipStream_t st);
 
+bool gemm_large_swiglu_supported(int dtype, int M, int N, int K);
+int launch_gemm_large_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st);
+
 int launch_gemm(int dtype, const void* X, const void* Wp, float* out, int M, int N, int K, int64_t ld, int max_split,
                 Partials* res, hipStream_t st) {
   *res = single_slot(out, (int64_t)M * ld, ld);
@@ -243,8 +246,12 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
     return rc;
   if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, &pr, st))) return rc;
   if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
-  if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
-  if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
+  if (gemm_large_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {  // several sequences: SwiGLU in the GEMM's epilogue
+    if ((rc = launch_gemm_large_swiglu(m.dtype, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
+  } else {
+    if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
+    if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
+  }
   if ((rc = launch_gemm(m.dtype, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, &pr, st))) return rc;
   return launch_residual_rmsnorm(m.dtype, x, pr, g_next, xn_next, rows, m.d, m.rms_eps, st);
 }
