@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E peak
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
 # of known size; see profiles/gemm_w64_cfg3_step_1k_pmc.md).  Measured offline; not re-measured by this script.
-TRAFFIC_W64 = {"fetch_bytes_per_launch": 112.62e6, "write_bytes_per_launch": 9.39e6,
+TRAFFIC_W64 = {"fetch_bytes_per_launch": 110.88e6, "write_bytes_per_launch": 6.33e6,
                "source": "profiles/gemm_w64_cfg3_step_1k_pmc.md"}
 
 
@@ -295,7 +295,7 @@ def main():
         "hbm": {"algorithmic_bytes_per_step": ab["total"], "achieved_GBps": step_gbps,
                 "frac_of_peak": step_gbps / HBM_PEAK_GBPS,
                 "kv_share_of_bytes": (ab["kv_prefix"] + ab["kv_tree"]) / ab["total"]},
-        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128," + ("f16_t" if w.dtype == "fp16" else "bf16_t") + "> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head)",
+        "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128," + ("f16_t" if w.dtype == "fp16" else "bf16_t") + ",*> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head; the last template argument selects the epilogue: partial sums, or SwiGLU for gate/up)",
                      "bound": "hbm", "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gemm_gbps / HBM_PEAK_GBPS,
                      "traffic": TRAFFIC_W64["fetch_bytes_per_launch"] + TRAFFIC_W64["write_bytes_per_launch"],

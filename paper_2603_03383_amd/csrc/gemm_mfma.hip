@@ -16,6 +16,10 @@
 //     the ranges line up with the bands (plan_gemm).  A range that ends inside a band leaves a partial sum; partial sums go
 //     to numbered slots of a workspace and the consumer adds slots 0..count-1 in that fixed order, so the
 //     result is deterministic (no floating-point atomics).
+//   * SWIGLU (the gate/up matrix, whose gate and up tiles alternate in the packed order, run with whole bands per
+//     workgroup): waves 0/2 hold the gate columns and waves 1/3 the up columns of the same 32 features; at the end of
+//     a band the up sums cross to their partner through LDS and SiLU(gate) * up is written as E, so neither the
+//     fp32 sums nor a second kernel are needed.
 #include "kernels.h"
 
 namespace mdz {
@@ -23,10 +27,14 @@ namespace mdz {
 typedef f32x16_t f32x16;
 typedef u32x4_t u32x4;
 
-template <int WPB, int NT, int MT, int CK, typename E>
+__device__ inline float silu_mfma(float v) { return v / (1.0f + expf(-v)); }
+
+template <int WPB, int NT, int MT, int CK, typename E, bool SWIGLU = false>
 __global__ void __launch_bounds__(WPB * 64)
     gemm_mfma_kernel(const E* __restrict__ X, int M, int K, const E* __restrict__ Wp, int n_tiles,
-                     int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride, int whole_bands) {
+                     int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride, int whole_bands,
+                     E* __restrict__ Uout = nullptr) {
+  static_assert(!SWIGLU || (WPB == 4 && NT == 1), "the SwiGLU epilogue pairs waves 0/1 and 2/3");
   constexpr int ROWS = MT * 32;
   constexpr int KH = CK / 32;                       // MFMA k-steps per half stage
   constexpr int LROW = CK * 2 + 16;                 // bytes per staged X row (16 B pad)
@@ -132,6 +140,34 @@ __global__ void __launch_bounds__(WPB * 64)
   // D layout of the 32x32 MFMA: lane holds column (lane % 32); register r is row 8*(r/4) + 4*(lane/32) + r%4.
   auto flush = [&]() {
     const int b = cb;
+    if constexpr (SWIGLU) {
+      // exchange buffer behind the two X stages: [pair][row][33] floats
+      float* xch = reinterpret_cast<float*>(lds_raw + 2 * ROWS * LROW) + (wave >> 1) * ROWS * 33;
+      const int col = lane & 31, rbase = (lane >> 5) * 4;
+      if (wave & 1) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) xch[(mt * 32 + 8 * (r >> 2) + rbase + (r & 3)) * 33 + col] = acc[0][mt][r];
+      }
+      __syncthreads();
+      const int tile = b * WPB + wave;  // even waves: a gate tile; its features are 16 * tile .. + 31
+      if (!(wave & 1) && tile + 1 < n_tiles) {
+        int F = n_tiles * 16;  // (M * F < 2^31: checked on the host; opaque so that the row offsets are not hoisted)
+        asm volatile("" : "+s"(F));
+        E* urow = Uout + tile * 16 + col;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = mt * 32 + 8 * (r >> 2) + rbase + (r & 3);
+            if (m < M) urow[m * F] = from_float<E>(silu_mfma(acc[0][mt][r]) * xch[m * 33 + col]);
+          }
+      }
+      __syncthreads();
+      zero_acc();
+      return;
+    }
     // slot = this workgroup's rank among the ranges that touch the band (see Partials::count)
     const int slot = whole_bands ? 0 : (int)(w - Partials::owner((uint32_t)b * n_stages, U, G));
     float* out = P + (int64_t)slot * part_stride;
@@ -341,6 +377,43 @@ static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, in
 #undef MDZ_GEMM_CASE
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
+}
+
+// The gate/up GEMM with the SwiGLU in its epilogue: U [M][N / 2] of the storage type.  Whole bands per workgroup, so
+// it is taken only where the bands nearly fill the chip (or fill it a whole number of times).
+bool gemm_mfma_swiglu_supported(int dtype, int M, int N, int K) {
+  if (!gemm_mfma_supported(dtype, M, N, K) || N % 128 != 0) return false;
+  const int bands = N / 128;
+  return (bands >= kNumCU * 5 / 8 && bands <= kNumCU) || (bands > kNumCU && bands % kNumCU == 0);
+}
+
+template <typename E>
+static int launch_gemm_mfma_swiglu_t(const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {
+  ProfScope prof_(M <= 32 ? PROF_GEMM_W32 : PROF_GEMM_W64, st);
+  const int n_tiles = N / 32, n_stages = K / 128, bands = N / 128;
+  const int grid = bands < kNumCU ? bands : kNumCU;
+  MDZ_REQUIRE((int64_t)bands * n_stages * grid < (int64_t)1 << 31 && (int64_t)M * N < (int64_t)1 << 31, MDZ_ESHAPE,
+              "gemm: %d x %d units overflow", bands, n_stages);
+#define MDZ_SWIGLU_CASE(MT)                                                                                         \
+  {                                                                                                                  \
+    constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 2 * MT * 32 * 33 * 4;                                   \
+    static bool attr_set = false;                                                                                    \
+    if (!attr_set) {                                                                                                 \
+      MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<4, 1, MT, 128, E, true>),           \
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));                           \
+      attr_set = true;                                                                                               \
+    }                                                                                                                \
+    gemm_mfma_kernel<4, 1, MT, 128, E, true><<<grid, 256, lds_bytes, st>>>((const E*)X, M, K, (const E*)Wp, n_tiles, \
+                                                                           n_stages, nullptr, 0, 0, 1, (E*)U);       \
+  }
+  if (M <= 32) MDZ_SWIGLU_CASE(1) else MDZ_SWIGLU_CASE(2)
+#undef MDZ_SWIGLU_CASE
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+int launch_gemm_mfma_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_gemm_mfma_swiglu_t<E>(X, Wp, U, M, N, K, st));
 }
 
 int launch_gemm_mfma(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,

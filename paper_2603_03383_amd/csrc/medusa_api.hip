@@ -33,6 +33,8 @@ int gemm_large_slots(int M, int N, int K);
 int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
                       int64_t part_stride, Partials* res, hipStream_t st);
 
+bool gemm_mfma_swiglu_supported(int dtype, int M, int N, int K);
+int launch_gemm_mfma_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st);
 bool gemm_large_swiglu_supported(int dtype, int M, int N, int K);
 int launch_gemm_large_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st);
 
@@ -246,8 +248,11 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
     return rc;
   if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, &pr, st))) return rc;
   if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
-  if (gemm_large_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {  // several sequences: SwiGLU in the GEMM's epilogue
+  // SwiGLU in the GEMM's epilogue where a workgroup ends up with whole gate/up column pairs
+  if (gemm_large_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {
     if ((rc = launch_gemm_large_swiglu(m.dtype, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
+  } else if (rows <= 64 && gemm_mfma_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {
+    if ((rc = launch_gemm_mfma_swiglu(m.dtype, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
   } else {
     if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
     if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
