@@ -67,6 +67,11 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
   for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
 }
 
+template <typename T>
+struct alignas(sizeof(T) * 4) Quad {
+  T v[4];
+};
+
 // Fast path for d == 4 * blockDim (d = 4096 with 1024 threads): every thread owns one float4 of the row, all
 // partial loads are issued at once, and the row never leaves registers between the two halves.
 template <typename T>
@@ -80,12 +85,19 @@ __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __re
   float4 v = *reinterpret_cast<const float4*>(x + (int64_t)r * d + i);
   if (P) {
     const int n_part = part.count(i);  // band widths are multiples of 32, so one count covers the float4
-    for (int s = 0; s < n_part; ++s) {
-      float4 p = *reinterpret_cast<const float4*>(P + (int64_t)s * part_stride + (int64_t)r * ldp + i);
-      v.x += p.x;
-      v.y += p.y;
-      v.z += p.z;
-      v.w += p.w;
+    // the first twelve slots (the most the streaming GEMM makes) are requested together, then added in slot order
+    constexpr int kTogether = 12;
+    const float* src = P + (int64_t)r * ldp + i;
+    float4 p[kTogether];
+#pragma unroll
+    for (int s = 0; s < kTogether; ++s)
+      if (s < n_part) p[s] = *reinterpret_cast<const float4*>(src + (int64_t)s * part_stride);
+#pragma unroll
+    for (int s = 0; s < kTogether; ++s)
+      if (s < n_part) v.x += p[s].x, v.y += p[s].y, v.z += p[s].z, v.w += p[s].w;
+    for (int s = kTogether; s < n_part; ++s) {
+      const float4 q = *reinterpret_cast<const float4*>(src + (int64_t)s * part_stride);
+      v.x += q.x, v.y += q.y, v.z += q.z, v.w += q.w;
     }
     *reinterpret_cast<float4*>(x + (int64_t)r * d + i) = v;
   }
@@ -97,18 +109,20 @@ __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __re
 #pragma unroll
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float rs = 1.0f / sqrtf(tot / (float)d + eps);
-  T o[4] = {from_float<T>(v.x * rs * to_float(g[i])), from_float<T>(v.y * rs * to_float(g[i + 1])),
-            from_float<T>(v.z * rs * to_float(g[i + 2])), from_float<T>(v.w * rs * to_float(g[i + 3]))};
-  T* dst = xn + (int64_t)r * d + i;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) dst[j] = o[j];
+  const Quad<T> gi = *reinterpret_cast<const Quad<T>*>(g + i);  // gains and output: one 8- or 16-byte access each
+  Quad<T> o;
+  o.v[0] = from_float<T>(v.x * rs * to_float(gi.v[0]));
+  o.v[1] = from_float<T>(v.y * rs * to_float(gi.v[1]));
+  o.v[2] = from_float<T>(v.z * rs * to_float(gi.v[2]));
+  o.v[3] = from_float<T>(v.w * rs * to_float(gi.v[3]));
+  *reinterpret_cast<Quad<T>*>(xn + (int64_t)r * d + i) = o;
 }
 
 int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
                             float eps, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
-  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0)
+  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0)
     MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
   else
     MDZ_WITH_ELEM(dtype, (residual_rmsnorm_kernel<E><<<rows, 256, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
