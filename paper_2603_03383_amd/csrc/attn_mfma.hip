@@ -492,18 +492,43 @@ __global__ void __launch_bounds__(256)
   const int qq = blockIdx.z * 16 + (threadIdx.x >> 4), f0 = (threadIdx.x & 15) * 8;
   const int64_t p0 = (int64_t)(b * n_heads + h) * n_splits;
   float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((p0 + s) * 2 + 0) * kTQ + qq]);
   float L = 0.f;
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
-    L += w * part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
-    const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
-    const float4 v0 = po[0], v1 = po[1];
-    acc[0] += w * v0.x, acc[1] += w * v0.y, acc[2] += w * v0.z, acc[3] += w * v0.w;
-    acc[4] += w * v1.x, acc[5] += w * v1.y, acc[6] += w * v1.z, acc[7] += w * v1.w;
+  constexpr int kTogether = 8;  // up to eight splits: every load is requested before the first is used
+  if (n_splits <= kTogether) {
+    float ms[kTogether], ls[kTogether];
+    float4 v0[kTogether], v1[kTogether];
+#pragma unroll
+    for (int s = 0; s < kTogether; ++s)
+      if (s < n_splits) {
+        ms[s] = part_ml[((p0 + s) * 2 + 0) * kTQ + qq];
+        ls[s] = part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
+        const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
+        v0[s] = po[0], v1[s] = po[1];
+      }
+#pragma unroll
+    for (int s = 0; s < kTogether; ++s)
+      if (s < n_splits) M = fmaxf(M, ms[s]);
+#pragma unroll
+    for (int s = 0; s < kTogether; ++s)
+      if (s < n_splits) {
+        const float w = fast_exp2(ms[s] - M);
+        L += w * ls[s];
+        acc[0] += w * v0[s].x, acc[1] += w * v0[s].y, acc[2] += w * v0[s].z, acc[3] += w * v0[s].w;
+        acc[4] += w * v1[s].x, acc[5] += w * v1[s].y, acc[6] += w * v1[s].z, acc[7] += w * v1[s].w;
+      }
+  } else {
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((p0 + s) * 2 + 0) * kTQ + qq]);
+    for (int s = 0; s < n_splits; ++s) {
+      const float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
+      L += w * part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
+      const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
+      const float4 v0 = po[0], v1 = po[1];
+      acc[0] += w * v0.x, acc[1] += w * v0.y, acc[2] += w * v0.z, acc[3] += w * v0.w;
+      acc[4] += w * v1.x, acc[5] += w * v1.y, acc[6] += w * v1.z, acc[7] += w * v1.w;
+    }
   }
   const float inv = 1.0f / L;
   uint32_t pk[4];
