@@ -243,6 +243,15 @@ def test_small_bf16_layer_ragged_and_empty_prefix(S_list, max_prefix):
     _check_layer(r, S_list, "bf16")
 
 
+@pytest.mark.parametrize("ffn,S_list", [(10240, [40]), (12288, [0, 70]), (32768, [33]), (10208, [40])])
+def test_small_bf16_layer_wide_ffn_swiglu_in_the_gemm_epilogue(ffn, S_list):
+    """Gate/up matrices of 160, 192 and 512 column bands run whole bands per workgroup (one band, or two in turn) with
+    the SwiGLU in the GEMM's epilogue; 159.5 bands (ffn 10208) is the nearest width that takes the separate kernel."""
+    w = W.CONFIGS["cfg2_layer_bf16"].with_(d=256, n_heads=2, head_dim=128, ffn=ffn, name=f"wide_ffn{ffn}")
+    r = _layer_case(w, S_list, max(S_list), x_seed=f"wide_x{ffn}")
+    _check_layer(r, S_list, "bf16")
+
+
 def test_layer_is_deterministic_run_to_run():
     w = W.CONFIGS["cfg2_layer_bf16"].with_(d=512, n_heads=4, head_dim=128, ffn=1408, name="det_bf16")
     a = _layer_case(w, [130], 130)
