@@ -112,7 +112,8 @@ typedef struct {
   void* v;
   int32_t n_layers, batch, n_heads, head_dim, cap; /* n_heads: key/value heads (the heads the cache holds) */
   int32_t dtype; /* mdz_dtype */
-  int32_t quant; /* mdz_kv_quant; MDZ_KV_FP8E4M3 needs a 16-bit dtype, head_dim 128 and a tree of 64 nodes or 1 node */
+  int32_t quant; /* mdz_kv_quant; MDZ_KV_FP8E4M3 needs a 16-bit dtype, head_dim 128 and a tree of 64 nodes or 1 node (with
+                    the 1-node tree also a number of query heads that is a multiple of 4); anything else: MDZ_EUNSUPPORTED */
 } mdz_kv_desc;
 
 /* ---- introspection (all HOST out-pointers) ------------------------------------------------- */
