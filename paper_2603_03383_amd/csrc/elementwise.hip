@@ -402,25 +402,29 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
   return MDZ_OK;
 }
 
+// blockIdx.y = head: its partial sums start part_head_stride floats after the previous head's, its z rows n elements
 template <typename T>
-__global__ void head_residual_kernel(const T* __restrict__ h, Partials part, const T* __restrict__ b1,
+__global__ void head_residual_kernel(const T* __restrict__ h, Partials part, int64_t part_head_stride, HeadBiases b1s,
                                      T* __restrict__ z, int64_t n, int d) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n) return;
+  const int k = blockIdx.y;
+  const float* pp = part.p + k * part_head_stride;
+  const T* b1 = reinterpret_cast<const T*>(b1s.p[k]);
   float p = 0.f;
   const int n_part = part.count((int)(idx % d));
-  for (int s = 0; s < n_part; ++s) p += part.p[(int64_t)s * part.stride + idx];
+  for (int s = 0; s < n_part; ++s) p += pp[(int64_t)s * part.stride + idx];
   p += b1 ? to_float(b1[idx % d]) : 0.f;
-  z[idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
+  z[k * n + idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
 }
 
-int launch_head_residual(int dtype, const void* h, const Partials& pre, const void* b1, void* z, int B, int d,
-                         hipStream_t st) {
+int launch_head_residual(int dtype, const void* h, const Partials& pre, int64_t part_head_stride, const HeadBiases& b1s,
+                         int n_heads, void* z, int B, int d, hipStream_t st) {
   ProfScope prof_(PROF_MISC, st);
   int64_t n = (int64_t)B * d;
-  if (n == 0) return MDZ_OK;
-  unsigned blocks = (unsigned)((n + 255) / 256);
-  MDZ_WITH_ELEM(dtype, (head_residual_kernel<E><<<blocks, 256, 0, st>>>((const E*)h, pre, (const E*)b1, (E*)z, n, d)));
+  if (n == 0 || n_heads == 0) return MDZ_OK;
+  dim3 blocks((unsigned)((n + 255) / 256), n_heads);
+  MDZ_WITH_ELEM(dtype, (head_residual_kernel<E><<<blocks, 256, 0, st>>>((const E*)h, pre, part_head_stride, b1s, (E*)z, n, d)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

@@ -62,8 +62,13 @@ int launch_swiglu(int dtype, const Partials& gu, void* u, int M, int F, hipStrea
 int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, int B, int Tsrc, int d, void* h,
                        hipStream_t st);
 // z = h + SiLU(pre + b1) -> storage dtype
-int launch_head_residual(int dtype, const void* h, const Partials& pre, const void* b1, void* z, int B, int d,
-                         hipStream_t st);
+// z[k] = h + SiLU(sums of head k + bias of head k) for all n_heads Medusa heads in one launch: the partial sums of
+// head k start part_head_stride floats after those of head k - 1 (same slot layout), z [n_heads][B][d]
+struct HeadBiases {
+  const void* p[MDZ_MAX_HEADS];
+};
+int launch_head_residual(int dtype, const void* h, const Partials& pre, int64_t part_head_stride, const HeadBiases& b1s,
+                         int n_heads, void* z, int B, int d, hipStream_t st);
 // storage-dtype copy of fp32 rows (hidden_out)
 int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
 

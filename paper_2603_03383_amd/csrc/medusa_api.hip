@@ -147,7 +147,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
       int64_t e = gemm_part_elems(m.dtype, (int)rows, sh[0], sh[1]) * 4;
       layer_part = e > layer_part ? e : layer_part;
     }
-    int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d) * 4;
+    int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d) * 4 * (t->K > 0 ? t->K : 1);  // every head's sums at once
     w.part = take(layer_part > head_part ? layer_part : head_part);
   }
   w.q = take(rows * m.d * es);
@@ -155,7 +155,7 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
   w.u = take(rows * m.ffn * es);
   w.logits = take(rows * (int64_t)m.vocab * 4);
   w.h = take((int64_t)B * m.d * es);
-  w.z = take((int64_t)B * m.d * es);
+  w.z = take((int64_t)B * m.d * es * (t->K > 0 ? t->K : 1));
   w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
   {  // candidate lists of the selection kernels: the verify step's rows, or the heads' B * (K + 1) rows
     const int64_t head_rows = (int64_t)B * (t->K + 1);
@@ -424,13 +424,22 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
     if ((rc = launch_gemm(m.dtype, h, w->lm_head, hl, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if (!batched && (rc = launch_topk(hl, B, m.vocab, ld, 1, cand_flat, t->n_cand, wsb + L.sel, L.sel_bytes, st))) return rc;
   }
+  // the K first-layer GEMMs (each into its own partial-sum region), one launch for the K residual blocks, then the
+  // K vocabulary projections back to back
+  const int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d);
+  const int64_t zrow = (int64_t)B * m.d * elem_bytes(m.dtype);
+  HeadBiases b1s{};
+  for (int k = 0; k < t->K; ++k) {
+    b1s.p[k] = w->head_b1 ? w->head_b1[k] : nullptr;
+    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part + k * head_part, B, m.d, m.d, m.d, max_split_for(B), &pr, st)))
+      return rc;
+  }
+  pr.p = part;
+  if ((rc = launch_head_residual(m.dtype, h, pr, head_part, b1s, t->K, z, B, m.d, st))) return rc;
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
-    const void* b1 = w->head_b1 ? w->head_b1[k] : nullptr;
-    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part, B, m.d, m.d, m.d, max_split_for(B), &pr, st))) return rc;
-    if ((rc = launch_head_residual(m.dtype, h, pr, b1, z, B, m.d, st))) return rc;
     float* lk = hl + (int64_t)(k + 1) * V;
-    if ((rc = launch_gemm(m.dtype, z, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
+    if ((rc = launch_gemm(m.dtype, (char*)z + k * zrow, w->head_lm[k], lk, B, m.vocab, m.d, ld, 1, &pr, st))) return rc;
     if (!batched &&
         (rc = launch_topk(lk, B, m.vocab, ld, t->caps[k], cand_flat + seg, t->n_cand, wsb + L.sel, L.sel_bytes, st)))
       return rc;
