@@ -22,12 +22,24 @@ __device__ inline float block_sum_256(float v, float* smem4) {
 }
 
 template <typename T>
+struct alignas(sizeof(T) * 4) Quad {
+  T v[4];
+};
+
+template <typename T>
 __global__ void embed_kernel(const T* __restrict__ embed, const int32_t* __restrict__ tokens, float* __restrict__ x,
                              int d, int vocab) {
   int r = blockIdx.x;
   int tok = tokens[r];
   tok = min(max(tok, 0), vocab - 1);
   const T* src = embed + (int64_t)tok * d;
+  if (d % 4 == 0 && (reinterpret_cast<uintptr_t>(embed) | reinterpret_cast<uintptr_t>(x)) % 16 == 0) {  // four elements per thread
+    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
+      const Quad<T> q = *reinterpret_cast<const Quad<T>*>(src + i);
+      *reinterpret_cast<float4*>(x + (int64_t)r * d + i) = float4{to_float(q.v[0]), to_float(q.v[1]), to_float(q.v[2]), to_float(q.v[3])};
+    }
+    return;
+  }
   for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)r * d + i] = to_float(src[i]);
 }
 
@@ -35,7 +47,7 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
                  hipStream_t st) {
   ProfScope prof_(PROF_EMBED, st);
   if (rows == 0) return MDZ_OK;
-  MDZ_WITH_ELEM(dtype, (embed_kernel<E><<<rows, 256, 0, st>>>((const E*)embed, tokens, x, d, vocab)));
+  MDZ_WITH_ELEM(dtype, (embed_kernel<E><<<rows, 1024, 0, st>>>((const E*)embed, tokens, x, d, vocab)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
@@ -66,11 +78,6 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
   float rs = 1.0f / sqrtf(ss / (float)d + eps);
   for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
 }
-
-template <typename T>
-struct alignas(sizeof(T) * 4) Quad {
-  T v[4];
-};
 
 // Fast path for d == 4 * blockDim (d = 4096 with 1024 threads): every thread owns one float4 of the row, all
 // partial loads are issued at once, and the row never leaves registers between the two halves.
@@ -390,6 +397,11 @@ __global__ void gather_rows_kernel(const T* __restrict__ hidden, const int32_t* 
   int b = blockIdx.x;
   int r = src_row ? min(max(src_row[b], 0), Tsrc - 1) : 0;
   const T* src = hidden + ((int64_t)b * Tsrc + r) * d;
+  if (d % 4 == 0 && (reinterpret_cast<uintptr_t>(hidden) | reinterpret_cast<uintptr_t>(h)) % 16 == 0) {  // four elements per thread
+    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4)
+      *reinterpret_cast<Quad<T>*>(h + (int64_t)b * d + i) = *reinterpret_cast<const Quad<T>*>(src + i);
+    return;
+  }
   for (int i = threadIdx.x; i < d; i += blockDim.x) h[(int64_t)b * d + i] = src[i];
 }
 
@@ -397,7 +409,7 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
                        hipStream_t st) {
   ProfScope prof_(PROF_MISC, st);
   if (B == 0) return MDZ_OK;
-  MDZ_WITH_ELEM(dtype, (gather_rows_kernel<E><<<B, 256, 0, st>>>((const E*)hidden, src_row, Tsrc, d, (E*)h)));
+  MDZ_WITH_ELEM(dtype, (gather_rows_kernel<E><<<B, 1024, 0, st>>>((const E*)hidden, src_row, Tsrc, d, (E*)h)));
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
