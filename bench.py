@@ -60,11 +60,11 @@ def build_device(w, with_heads):
                        dtype=w.dtype, tree=w.tree.name, n_kv_heads=w.n_kv_heads, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev)
     for l in range(w.n_layers):
         mats = [W.layer_weight(w, l, m, dev) for m in W.LAYER_MATS]
-        dm.add_layer(*mats, W.norm_gain(w, "g", dev), W.norm_gain(w, "g", dev))
+        dm.add_layer(*mats, W.norm_gain(w, f"layer{l}.g_attn", dev), W.norm_gain(w, f"layer{l}.g_ffn", dev))
         del mats
     dm.set_embed(W.embedding(w, dev))
     dm.set_lm_head(W.lm_head(w, dev))
-    dm.set_final_gain(W.norm_gain(w, "g", dev))
+    dm.set_final_gain(W.norm_gain(w, "g_final", dev))
     if with_heads:
         for k in range(1, w.n_medusa + 1):
             dm.add_medusa_head(W.medusa_w1(w, k, dev), None, W.medusa_lm(w, k, dev))
@@ -104,7 +104,7 @@ def cpu_baseline(w, with_heads, budget_s=20.0):
     t_layers, nl = 0.0, 0
     for l in range(w.n_layers):
         lw = {m: f32(W.layer_weight(w, l, m, gen)) for m in W.LAYER_MATS}
-        lw["g_attn"] = lw["g_ffn"] = np.ones(w.d, np.float32)
+        lw["g_attn"], lw["g_ffn"] = f32(W.norm_gain(w, f"layer{l}.g_attn", gen)), f32(W.norm_gain(w, f"layer{l}.g_ffn", gen))
         k, v = W.prefix_kv(w, l, 0, gen)
         kc = np.zeros((w.kv_heads, S + T, w.head_dim)); vc = np.zeros_like(kc)
         kc[:, :S] = f32(k); vc[:, :S] = f32(v)
@@ -115,7 +115,7 @@ def cpu_baseline(w, with_heads, budget_s=20.0):
         del lw, kc, vc
         if t_layers > budget_s:
             break
-    model = dict(cfg=cfg, g_final=np.ones(w.d, np.float32), lm_head=f32(W.lm_head(w, gen)))
+    model = dict(cfg=cfg, g_final=f32(W.norm_gain(w, "g_final", gen)), lm_head=f32(W.lm_head(w, gen)))
     t0 = time.perf_counter()
     hidden, logits = O._final(x, model)
     am = O.argmax_lowest(logits)

@@ -17,6 +17,12 @@ MUTATIONS = {
     "gate and up swapped": ("x = x + (silu(gate) * up)", "x = x + (silu(up) * gate)", "verify"),
     "transposed Wq": ('q = xn @ np.asarray(lw["wq"], dtype=F64).T', 'q = xn @ np.asarray(lw["wq"], dtype=F64)', "verify"),
     "head residual dropped": ("z = h + silu(pre)", "z = silu(pre)", "verify"),
+    "head bias dropped": ("pre = pre + np.asarray(head[\"b1\"], dtype=F64)", "pre = pre + 0.0", "verify"),
+    "final norm dropped": ('hidden = rmsnorm(x, model["g_final"], model["cfg"]["rms_eps"])', "hidden = np.asarray(x, dtype=F64)", "verify"),
+    "final norm without its gain": ('hidden = rmsnorm(x, model["g_final"], model["cfg"]["rms_eps"])', 'hidden = rmsnorm(x, 1.0, model["cfg"]["rms_eps"])', "verify"),
+    "LM head replaced by the embedding": ('logits = hidden @ np.asarray(model["lm_head"], dtype=F64).T', 'logits = hidden @ np.asarray(model["embed"], dtype=F64).T', "verify"),
+    "norm eps dropped": ("return x / np.sqrt(ms + eps) * np.asarray(g, dtype=F64)", "return x / np.sqrt(ms) * np.asarray(g, dtype=F64)", "verify"),
+    "norm gain dropped": ("return x / np.sqrt(ms + eps) * np.asarray(g, dtype=F64)", "return x / np.sqrt(ms + eps)", "verify"),
     "match against own node instead of parent": ("tree_tokens[n] != node_argmax[parent[n]]", "tree_tokens[n] != node_argmax[n]", "accept"),
     "compaction source": ("src[:A] = S + np.asarray(acc_nodes[:A])", "src[:A] = S + np.arange(A)", "accept or verify"),
     "tie to highest path": ("if n_ok > best_len:", "if n_ok >= best_len:", "accept"),

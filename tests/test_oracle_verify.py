@@ -143,6 +143,56 @@ def test_chain_tree_layer_matches_torch_library_ops(S):
     np.testing.assert_allclose(vc[:, S:], vref, rtol=0, atol=1e-12)
 
 
+def test_chain_tree_whole_step_matches_torch_library_ops_end_to_end():
+    """Embedding -> every layer -> final norm -> LM head -> argmax of a chain-shaped tree (ordinary causal decoding
+    of 6 tokens after a prefix) against PyTorch CPU library ops in float64, with non-unit gains everywhere
+    (final norm included) and an LM head that is a different tensor from the embedding."""
+    w = TINY
+    S = 9
+    model = U.oracle_model(w, dtype="fp64")
+    assert all(np.abs(lw[g] - 1.0).max() > 0.3 for lw in model["layers"] for g in ("g_attn", "g_ffn"))
+    assert np.abs(model["g_final"] - 1.0).max() > 0.3 and not np.array_equal(model["lm_head"], model["embed"])
+    chain = OT.build_tree((1, 1, 1, 1, 1), (1, 1, 1, 1, 1))
+    T = chain["T"]
+    tokens = W.random_tokens(w, "chain_step_tok", (T,)).numpy()
+    kpre = [W.normal(3, f"kpre{l}", (w.n_heads, S, w.head_dim)).numpy() for l in range(w.n_layers)]
+    vpre = [W.normal(3, f"vpre{l}", (w.n_heads, S, w.head_dim)).numpy() for l in range(w.n_layers)]
+    kc, vc = O.empty_cache(model["cfg"], S + T)
+    for l in range(w.n_layers):
+        kc[l][:, :S] = kpre[l]
+        vc[l][:, :S] = vpre[l]
+    got = O.tree_verify_step(tokens, model, kc, vc, S, chain)
+    # library-op reference
+    x = F.embedding(torch.tensor(tokens, dtype=torch.long), torch.tensor(model["embed"], dtype=torch.float64)).numpy()
+    for l in range(w.n_layers):
+        x, kref, vref = _torch_layer_reference(x, model["layers"][l], kpre[l], vpre[l], S, model["cfg"])
+        np.testing.assert_allclose(kc[l][:, S:], kref, rtol=0, atol=1e-11)
+        np.testing.assert_allclose(vc[l][:, S:], vref, rtol=0, atol=1e-11)
+    xt = torch.tensor(x)
+    hidden = F.rms_norm(xt, (w.d,), weight=torch.tensor(model["g_final"], dtype=torch.float64), eps=w.rms_eps)
+    logits = F.linear(hidden, torch.tensor(model["lm_head"], dtype=torch.float64))
+    np.testing.assert_allclose(got["hidden"], hidden.numpy(), rtol=0, atol=1e-11 * float(hidden.abs().max()))
+    np.testing.assert_allclose(got["logits"], logits.numpy(), rtol=0, atol=1e-11 * float(logits.abs().max()))
+    assert got["node_argmax"].tolist() == torch.argmax(logits, dim=1).tolist()
+    # the hidden the step returns is what the Medusa heads read: its base-head logits are the step's logits
+    heads = O.medusa_heads(got["hidden"][2], model, U.oracle_tree(w))
+    np.testing.assert_allclose(heads["head_logits"][0], logits[2].numpy(), rtol=0, atol=1e-11 * float(logits.abs().max()))
+
+
+def test_heads_with_bias_against_torch_ops(tiny):
+    """The optional bias of a head's residual block enters before the SiLU."""
+    w = TINY.with_(head_bias_std=1.0)
+    model, tree = U.oracle_model(w), tiny["tree"]
+    assert all(hd["b1"] is not None and np.abs(hd["b1"]).max() > 1.0 for hd in model["medusa"])
+    h = W.hidden_state(w, "heads_hb", 1).numpy()[0]
+    out = O.medusa_heads(h, model, tree)
+    ht = torch.tensor(h, dtype=torch.float64)
+    for k, hd in enumerate(model["medusa"]):
+        z = ht + F.silu(F.linear(ht, torch.tensor(hd["w1"], dtype=torch.float64), torch.tensor(hd["b1"], dtype=torch.float64)))
+        lg = F.linear(z, torch.tensor(hd["lm"], dtype=torch.float64))
+        np.testing.assert_allclose(out["head_logits"][k + 1], lg.numpy(), rtol=1e-12, atol=1e-12)
+
+
 def test_rope_properties():
     hd = 64
     q = W.normal(1, "rq", (3, hd)).numpy().astype(np.float64)

@@ -25,8 +25,8 @@ def oracle_tree(w: W.Workload) -> dict:
 
 def oracle_layer(w: W.Workload, layer: int, device="cpu") -> dict:
     lw = {m: to_np(W.layer_weight(w, layer, m, device)) for m in W.LAYER_MATS}
-    lw["g_attn"] = to_np(W.norm_gain(w, f"layer{layer}.g_attn"))
-    lw["g_ffn"] = to_np(W.norm_gain(w, f"layer{layer}.g_ffn"))
+    lw["g_attn"] = to_np(W.norm_gain(w, f"layer{layer}.g_attn", device))
+    lw["g_ffn"] = to_np(W.norm_gain(w, f"layer{layer}.g_ffn", device))
     return lw
 
 
@@ -34,10 +34,11 @@ def oracle_model(w: W.Workload, device="cpu", heads=True, dtype=None) -> dict:
     m = dict(cfg=oracle_cfg(w, dtype),
              layers=[oracle_layer(w, l, device) for l in range(w.n_layers)],
              embed=to_np(W.embedding(w, device)), lm_head=to_np(W.lm_head(w, device)),
-             g_final=to_np(W.norm_gain(w, "g_final")), medusa=[])
+             g_final=to_np(W.norm_gain(w, "g_final", device)), medusa=[])
     if heads:
         for k in range(1, w.n_medusa + 1):
-            m["medusa"].append(dict(w1=to_np(W.medusa_w1(w, k, device)), b1=None,
+            b1 = W.medusa_b1(w, k, device)
+            m["medusa"].append(dict(w1=to_np(W.medusa_w1(w, k, device)), b1=None if b1 is None else to_np(b1),
                                     lm=to_np(W.medusa_lm(w, k, device))))
     return m
 

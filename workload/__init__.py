@@ -164,6 +164,8 @@ class Workload:
     seed: int = BASE_SEED
     n_kv_heads: int = 0        # key/value heads (grouped-query attention); 0 = n_heads (plain multi-head attention)
     kv_quant: str = ""         # "" | "fp8e4m3": cache rows stored as 8-bit codes with one fp32 scale per row
+    gain_std: float = 0.3      # RMSNorm gains are 1 + gain_std * z (0: all ones)
+    head_bias_std: float = 0.0  # Medusa-head bias b1 ~ head_bias_std * z (0: the heads have no bias)
 
     @property
     def kv_heads(self) -> int:
@@ -239,8 +241,12 @@ def layer_weight(w: Workload, layer: int, mat: str, device="cpu") -> torch.Tenso
 
 
 def norm_gain(w: Workload, name: str, device="cpu") -> torch.Tensor:
-    """RMSNorm gains are all ones in every workload (kept as tensors so the path reads them)."""
-    return torch.ones(w.d, dtype=w.torch_dtype, device=device)
+    """RMSNorm gains [d]: 1 + gain_std * z, seeded per gain vector (``name`` = "layer3.g_attn", "g_final", ...),
+    rounded to the storage dtype; all ones when gain_std is 0."""
+    if w.gain_std == 0.0:
+        return torch.ones(w.d, dtype=w.torch_dtype, device=device)
+    z = normal(w.seed, f"gain.{name}", (w.d,), w.gain_std, torch.float32, device)
+    return (z + 1.0).to(w.torch_dtype)
 
 
 def embedding(w: Workload, device="cpu") -> torch.Tensor:
@@ -254,6 +260,13 @@ def lm_head(w: Workload, device="cpu") -> torch.Tensor:
 
 def medusa_w1(w: Workload, k: int, device="cpu") -> torch.Tensor:
     return normal(w.seed, f"medusa{k}.w1", (w.d, w.d), w.weight_std, w.torch_dtype, device)
+
+
+def medusa_b1(w: Workload, k: int, device="cpu"):
+    """Bias [d] of Medusa head k's residual block, or None when the workload's heads have none."""
+    if w.head_bias_std == 0.0:
+        return None
+    return normal(w.seed, f"medusa{k}.b1", (w.d,), w.head_bias_std, w.torch_dtype, device)
 
 
 def medusa_lm(w: Workload, k: int, device="cpu") -> torch.Tensor:
