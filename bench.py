@@ -23,10 +23,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E peak
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
-# of known size; see profiles/gemm_w64_cfg3_step_1k_pmc.md).  Measured offline; not re-measured by this script.
-TRAFFIC_W64 = {"fetch_bytes_per_launch": 110.88e6, "write_bytes_per_launch": 6.33e6,
-               "source": "profiles/gemm_w64_cfg3_step_1k_pmc.md"}
+MFMA_PEAK_TFLOPS = 2500.0         # dense bf16 / fp16 matrix-core peak
+TRAFFIC_PROFILE = "profiles/gemm_w64_cfg3_step_1k_pmc.md"
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE / WRITE_SIZE counters saw them, read from
+    the committed counter summary (its last line is machine readable: `traffic_json: {...}`, written by the run that
+    produced the file, with the source revision it measured).  None when the summary is absent or has no such line:
+    this script does not re-measure counters."""
+    try:
+        lines = open(os.path.join(ROOT, TRAFFIC_PROFILE)).read().splitlines()
+    except OSError:
+        return None
+    for ln in reversed(lines):
+        if ln.startswith("traffic_json:"):
+            d = json.loads(ln[len("traffic_json:"):])
+            d["source"] = TRAFFIC_PROFILE
+            return d
+    return None
 
 
 def algorithmic_bytes(w, with_heads: bool):
@@ -69,14 +84,155 @@ def build_device(w, with_heads):
         for k in range(1, w.n_medusa + 1):
             dm.add_medusa_head(W.medusa_w1(w, k, dev), None, W.medusa_lm(w, k, dev))
     dm.finalize()
+    kv, max_prefix = build_kv(dm, w)
+    return dm, kv, max_prefix
+
+
+def build_kv(dm, w):
+    """KV cache of workload `w` (its batch and seeded prefix rows) for the model `dm`."""
+    import torch
+    import workload as W
+    import paper_2603_03383_amd as P
     max_prefix = max(w.prefix) + (w.n_medusa + 1)
     kv = P.DeviceKV(dm, batch=w.batch, cap=max_prefix + w.tree.n_nodes, quant=w.kv_quant)
     for b in range(w.batch):
         for l in range(w.n_layers):
-            k, v = W.prefix_kv(w, l, b, dev)
+            k, v = W.prefix_kv(w, l, b, dm.device)
             kv.write(l, b, 0, k, v)
     torch.cuda.empty_cache()
-    return dm, kv, max_prefix
+    return kv, max_prefix
+
+
+def timed(fn, warmup, steps):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def profiled(fn, steps, launches_per_step):
+    """{family: {launches, total_us, ...}} over `steps` instrumented runs of fn (HIP events around every launch)."""
+    import torch
+    import paper_2603_03383_amd as P
+    P.medusa_profile_begin(steps * launches_per_step)
+    for _ in range(steps):
+        fn()
+    prof = P.medusa_profile_end()
+    torch.cuda.synchronize()
+    return prof
+
+
+def other_configs(dm, w3, steps, warmup):
+    """The benchmark configurations beside the headline one, on the SAME 32-layer weights (only the KV cache, the
+    batch and the entry point change): config 2 (tree_verify_layer alone, prefix 512), config 4 (the whole step at
+    prefixes 4096 / 8192 / 16384 with the KV-versus-weights byte share) and config 5 (16 ragged sequences)."""
+    import torch
+    import workload as W
+    import paper_2603_03383_amd as P
+    out = {}
+    T = w3.tree.n_nodes
+    dev = dm.device
+
+    # ---- config 2: one layer per call, prefix 512.  Call i uses the weights and the cache of layer i mod 32, so
+    # consecutive calls stream 32 different 405 MB weight sets (13 GB in rotation): nothing is served again from the
+    # 256 MB memory-side cache.
+    w2 = W.CONFIGS["cfg2_layer_bf16"].with_(n_layers=w3.n_layers)
+    kv2, mp2 = build_kv(dm, w2)
+    ws = dm.workspace(1, mp2)
+    seq0 = torch.tensor(w2.prefix, dtype=torch.int32, device=dev)
+    seq = seq0.clone()
+    x = W.hidden_state(w2, "bench_x", T, dev).float()
+    it = [0]
+
+    def layer_call():
+        l = it[0] % w3.n_layers
+        it[0] += 1
+        P.tree_verify_layer(dm.desc, dm.layer(l), l, x, kv2.desc, seq, 1, mp2, ws)
+
+    n2 = max(steps, 32)
+    ms2 = timed(layer_call, 8, n2)
+    ab = algorithmic_bytes(w2.with_(n_layers=1), False)
+    b2 = ab["weights_layers"] + ab["kv_prefix"] + ab["kv_tree"]
+    prof = profiled(layer_call, 32, 16)
+    out["cfg2_layer_bf16"] = {
+        "entry_point": "tree_verify_layer", "prefix": 512, "calls_timed": n2, "us_per_call": ms2 * 1e3,
+        "layer_calls_per_s": 1e3 / ms2, "algorithmic_bytes_per_call": b2,
+        "achieved_GBps": b2 / (ms2 * 1e-3) / 1e9, "frac_of_peak": b2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "weight_sets_in_rotation": w3.n_layers,
+        "kernel_us_per_call": {k: v["total_us"] / 32 for k, v in prof.items()}}
+    del kv2, ws
+
+    # ---- config 4: the whole step (heads + verify + accept + compact) at long prefixes
+    hidden = W.hidden_state(w3, "bench_h", 1, dev).view(1, 1, w3.d)
+    root = W.random_tokens(w3, "bench_root", (1,), dev)
+    n4 = min(steps, 10)
+    out["cfg4_long_prefix"] = {}
+    for S in (4096, 8192, 16384):
+        w4 = W.CONFIGS["cfg4_step_%dk" % (S // 1024)]
+        kv4, mp4 = build_kv(dm, w4)
+        buf = P.StepBuffers(dm, 1, mp4)
+        buf.tree_tokens.copy_(W.random_tokens(w4, "bench_tree", (1, T), dev))
+        s0 = torch.tensor(w4.prefix, dtype=torch.int32, device=dev)
+        sl = s0.clone()
+
+        def step4():
+            sl.copy_(s0)
+            P.run_step(dm, kv4, buf, hidden, None, root, sl, with_heads=True)
+
+        ms4 = timed(step4, warmup, n4)
+        prof = profiled(step4, 3, w3.n_layers * 12 + 64)
+        ab = algorithmic_bytes(w4, True)
+        kvb = ab["kv_prefix"] + ab["kv_tree"]
+        att_us = prof.get("attention", {"total_us": 0.0})["total_us"] / 3
+        out["cfg4_long_prefix"][str(S)] = {
+            "ms_per_step": ms4, "steps_per_s": 1e3 / ms4, "algorithmic_bytes_per_step": ab["total"],
+            "achieved_GBps": ab["total"] / (ms4 * 1e-3) / 1e9, "frac_of_peak": ab["total"] / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "kv_share_of_bytes": kvb / ab["total"], "kv_share_of_verify_bytes": kvb / (ab["total"] - ab["heads"]),
+            "weights_share_of_bytes": (ab["gemm"]) / ab["total"],
+            "attention_us_per_step": att_us, "attention_GBps": kvb / (att_us * 1e-6) / 1e9 if att_us else None}
+        del kv4, buf
+        torch.cuda.empty_cache()
+
+    # ---- config 5: 16 ragged sequences (M = 1024 rows: the GEMMs are bound by the matrix cores)
+    w5 = W.CONFIGS["cfg5_ragged_b16"]
+    Bn = w5.batch
+    kv5, mp5 = build_kv(dm, w5)
+    buf = P.StepBuffers(dm, Bn, mp5)
+    buf.tree_tokens.copy_(W.random_tokens(w5, "bench_tree", (Bn, T), dev))
+    h5 = W.hidden_state(w5, "bench_h", Bn, dev).view(Bn, 1, w5.d)
+    r5 = W.random_tokens(w5, "bench_root", (Bn,), dev)
+    s0 = torch.tensor(w5.prefix, dtype=torch.int32, device=dev)
+    sl = s0.clone()
+
+    def step5():
+        sl.copy_(s0)
+        P.run_step(dm, kv5, buf, h5, None, r5, sl, with_heads=True)
+
+    n5 = min(steps, 5)
+    ms5 = timed(step5, 2, n5)
+    prof = profiled(step5, 2, w3.n_layers * 12 + 64)
+    ab = algorithmic_bytes(w5, True)
+    gl = prof.get("gemm_large", {"total_us": 0.0, "launches": 0})
+    elems = w5.n_layers * (2 * w5.d * w5.d + 2 * w5.kv_heads * w5.head_dim * w5.d + 3 * w5.d * w5.ffn) + w5.vocab * w5.d
+    flops = 2.0 * Bn * T * elems
+    tf = flops / (gl["total_us"] / 2 * 1e-6) / 1e12 if gl["total_us"] else None
+    att_us = prof.get("attention", {"total_us": 0.0})["total_us"] / 2
+    kvb = ab["kv_prefix"] + ab["kv_tree"]
+    out["cfg5_ragged_b16"] = {
+        "ms_per_step": ms5, "steps_per_s": 1e3 / ms5, "sequence_steps_per_s": Bn * 1e3 / ms5, "prefix": list(w5.prefix),
+        "gemm": {"bound": "mfma", "flops_per_step": flops, "us_per_step": gl["total_us"] / 2, "achieved_TFLOPs": tf,
+                 "peak_TFLOPs": MFMA_PEAK_TFLOPS, "frac": tf / MFMA_PEAK_TFLOPS if tf else None},
+        "attention": {"bound": "hbm", "kv_bytes_per_step": kvb, "us_per_step": att_us,
+                      "achieved_GBps": kvb / (att_us * 1e-6) / 1e9 if att_us else None},
+        "kernel_us_per_step": {k: v["total_us"] / 2 for k, v in prof.items()}}
+    del kv5, buf
+    torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(w, with_heads, budget_s=20.0):
@@ -153,7 +309,8 @@ def main():
     ap.add_argument("--kv8", action="store_true", help="8-bit KV cache rows (E4M3 codes + one fp32 scale per row)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-extras", action="store_true",
-                    help="leave out the autoregressive baseline and the chained loop (profiling runs: only the timed steps are traced)")
+                    help="leave out the autoregressive baseline, the chained loop and the other configurations "
+                         "(profiling runs: only the timed steps are traced)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); run with --gpus 1",
@@ -191,22 +348,10 @@ def main():
         else:
             P.run_step(dm, kv, buf, hidden, None, root, seq_len, with_heads=with_heads)
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms = dt / args.steps * 1e3
+    ms = timed(one_step, args.warmup, args.steps)
 
     # instrumented steps: HIP events around every kernel launch, on the launch stream
-    P.medusa_profile_begin(args.steps * (w.n_layers * 12 + 64))
-    for _ in range(args.steps):
-        one_step()
-    prof = P.medusa_profile_end()
-    torch.cuda.synchronize()
+    prof = profiled(one_step, args.steps, w.n_layers * 12 + 64)
 
     # the autoregressive baseline (Section 4.1): the same weights and prefix, the single-node tree, timed the same way
     ar = None
@@ -272,6 +417,14 @@ def main():
     from paper_2603_03383_amd.stream_calib import read_ceiling
     ceil = read_ceiling(sizes=(154_500_000, 1_048_576_000), pool_bytes=4 << 30)
 
+    # configs 2, 4 and 5 on the same weights (default headline run only)
+    others = None
+    if args.workload == "cfg3_step_1k" and not (args.skip_extras or args.kv8 or args.no_heads or args.prefix is not None):
+        del kv, buf
+        torch.cuda.empty_cache()
+        others = other_configs(dm, w, args.steps, args.warmup)
+
+    traffic = traffic_from_profile()
     ab = algorithmic_bytes(w, with_heads)
     if layer_only:
         ab["gemm"] = ab["weights_layers"]
@@ -298,8 +451,8 @@ def main():
         "roofline": {"kernel": "gemm_mfma_kernel<4,1,2,128," + ("f16_t" if w.dtype == "fp16" else "bf16_t") + ",*> (gemm_w64: the QKV, O, gate/up, down launches of every layer and the LM head; the last template argument selects the epilogue: partial sums, or SwiGLU for gate/up)",
                      "bound": "hbm", "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gemm_gbps / HBM_PEAK_GBPS,
-                     "traffic": TRAFFIC_W64["fetch_bytes_per_launch"] + TRAFFIC_W64["write_bytes_per_launch"],
-                     "traffic_detail": TRAFFIC_W64,
+                     "traffic": (traffic["fetch_bytes_per_launch"] + traffic["write_bytes_per_launch"]) if traffic else None,
+                     "traffic_detail": traffic,
                      "algorithmic_bytes_per_launch": ab["gemm_w64"] / max(1.0, gemm["launches"] / args.steps),
                      "launches_per_step": gemm["launches"] / args.steps,
                      "avg_launch_us": gemm["total_us"] / max(1, gemm["launches"]),
@@ -311,6 +464,7 @@ def main():
         "kernel_launches_per_step": {k: v["launches"] / args.steps for k, v in prof.items()},
         "paper_metrics": ar,
         "chained_loop": chain,
+        "other_configs": others,
         "paper_context": "paper reports only ratios: 1.35x end-to-end on an NPU, fp16, L=128 (not comparable)",
     }
     if "gemm_large" in prof and prof["gemm_large"]["launches"]:
@@ -320,7 +474,7 @@ def main():
         flops = 2.0 * Bn * T * elems
         tf = flops / (gl["total_us"] / args.steps * 1e-6) / 1e12
         out["roofline"] = {"kernel": "gemm_large_kernel (every GEMM of the step at M = %d rows)" % (Bn * T), "bound": "mfma",
-                           "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
+                           "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS, "traffic": None,
                            "algorithmic_flops_per_launch": flops / (gl["launches"] / args.steps),
                            "launches_per_step": gl["launches"] / args.steps,
                            "avg_launch_us": gl["total_us"] / gl["launches"],
