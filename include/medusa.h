@@ -101,12 +101,17 @@ typedef struct {
   const void* const* head_lm; /* HOST array [n_medusa] */
 } mdz_weights;
 
+/* Bits the kernels OR into mdz_kv_desc.status (a device word the caller clears and reads when it chooses). */
+#define MDZ_STATUS_SEQ_RANGE 1 /* a seq_len[b] outside [0, max_prefix] reached a kernel and was clamped */
+
 /* HOST struct: the KV cache.  k and v are two device allocations of medusa_kv_bytes() bytes each whose
  * internal layout belongs to the library (tiled for the attention kernels); fill and inspect them with
- * medusa_kv_write / medusa_kv_read.  Zero-fill both once after allocating them: the attention kernels load whole
- * blocks of 32 slots and multiply the slots beyond a sequence's length by zero, which only finite contents survive.
- * cap = slots per sequence; a verify pass with prefix length S
- * writes slots S..S+T-1, so S + T <= cap is required. */
+ * medusa_kv_write / medusa_kv_read.  Call medusa_kv_init once after allocating them: the attention kernels load
+ * whole blocks of 32 slots and need the slots beyond a sequence's length to hold finite values.
+ * cap = slots per sequence; a verify pass with prefix length S writes slots S..S+T-1, so S + T <= cap is required.
+ * status (nullable): one int32 in device memory.  Lengths live on the device (a chained loop advances them without
+ * the host), so a length outside [0, max_prefix] cannot be rejected by the call: every kernel clamps it (no access
+ * leaves the cache) and tree_verify_layer / tree_verify_step / kv_compact OR MDZ_STATUS_SEQ_RANGE into *status. */
 typedef struct {
   void* k;
   void* v;
@@ -114,6 +119,7 @@ typedef struct {
   int32_t dtype; /* mdz_dtype */
   int32_t quant; /* mdz_kv_quant; MDZ_KV_FP8E4M3 needs a 16-bit dtype, head_dim 128 and a tree of 64 nodes or 1 node (with
                     the 1-node tree also a number of query heads that is a multiple of 4); anything else: MDZ_EUNSUPPORTED */
+  int32_t* status; /* device, nullable */
 } mdz_kv_desc;
 
 /* ---- introspection (all HOST out-pointers) ------------------------------------------------- */
@@ -130,46 +136,10 @@ int medusa_tree_tables(int tree, int32_t* parent, int32_t* depth, int32_t* cand_
 /* Never NULL; thread-local; valid until the next failing call on this thread. */
 const char* medusa_last_error(void);
 
-/* ---- optional per-kernel timing (benchmarks only) ---------------------------------------------- */
-
-/* Starts recording a HIP-event pair on the caller's stream around every kernel launch the library makes,
- * for at most max_launches launches (further ones are counted as dropped).  Creates its events here, so
- * hot-path calls still allocate nothing.  Process-global; not thread-safe. */
-int medusa_profile_begin(int max_launches);
-
-/* Stops recording, waits for the recorded events, and writes one text line per kernel family into the HOST
- * buffer `report`: "name,launches,total_us,min_us,max_us\n" (families: gemm_w64 / gemm_n64 / gemm_w32 /
- * gemm_n32 = the weight-streaming GEMM instantiated for 128- or 64-column bands and 64 or <= 32 rows,
- * gemm_portable, attention, rmsnorm, rope, swiglu, embed, select, accept, kv_compact, misc). */
-int medusa_profile_end(char* report, int64_t report_bytes);
-
-/* ---- calibration streams (benchmarks only) --------------------------------------------------- */
-
-/* Enqueues a pure read of `bytes` bytes at src (16 bytes per lane, every wave a contiguous range, n_workgroups
- * workgroups of 256 threads): the practical HBM read ceiling the weight-streaming kernels are compared with.
- * Only medusa_stream_read_bytes(bytes, n_workgroups) bytes are read (whole 8 KiB rounds per wave).  sink4: 4
- * device bytes that keep the loads alive. */
-int medusa_stream_read(const void* src, int64_t bytes, int n_workgroups, void* sink4, void* stream);
-int64_t medusa_stream_read_bytes(int64_t bytes, int n_workgroups);
-
-/* Enqueues a plain copy of `bytes` (multiple of 16) from src to dst: a transfer of known size for scaling
- * hardware byte counters. */
-int medusa_stream_copy(const void* src, void* dst, int64_t bytes, void* stream);
-
 /* ---- weight packing (one-time, outside any timed region) ------------------------------------ */
 
 /* Rows per packed tile for a dtype (32 for bf16 and fp16, 16 for fp32). */
 int medusa_pack_tile_rows(int dtype);
-
-/* Host-only introspection of the weight-streaming GEMM's work decomposition for X[M,K] x W[N,K]^T (bf16, M <= 64,
- * N % 32 == 0, K % 128 == 0), so that tests can audit it; nothing is enqueued.  The (column band, K-stage) units,
- * numbered band-major, are cut into `grid` equal contiguous ranges, range w = [floor(w*U/grid), floor((w+1)*U/grid)),
- * U = (N / band_cols rounded up) * n_stages; every range that touches a band writes one partial-sum slot of it.
- * max_split bounds the slots per band (1: whole bands only).  medusa_gemm_slot_count returns the number of slots the
- * consumers add for output column `col` (negative: error). */
-int medusa_gemm_plan(int dtype, int M, int N, int K, int max_split, int32_t* grid, int32_t* band_cols, int32_t* n_stages,
-                     int32_t* max_slots);
-int medusa_gemm_slot_count(int dtype, int M, int N, int K, int max_split, int col);
 
 /* Bytes of a packed [n_rows, k] matrix (bf16: n_rows rounded up to 128 and k to 256; fp32: n_rows to 16). */
 int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
@@ -187,6 +157,10 @@ int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
 
 /* Bytes of EACH of desc->k and desc->v (negative = mdz_status). */
 int64_t medusa_kv_bytes(const mdz_kv_desc* desc);
+
+/* Enqueues a fill of desc->k and desc->v (and of *desc->status, if given) with zeros: a kernel, not a memset, so
+ * the call may sit inside a captured graph. */
+int medusa_kv_init(const mdz_kv_desc* desc, void* stream);
 
 /* Copies n rows starting at slot pos0 of sequence `seq`, layer `layer`, between the cache and plain
  * buffers k_rows / v_rows laid out [n_heads][n][head_dim] in the storage dtype.  write: buffers ->

@@ -51,7 +51,8 @@ class Weights(C.Structure):
 
 class KvDesc(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("n_layers", C.c_int32), ("batch", C.c_int32),
-                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32), ("quant", C.c_int32)]
+                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32), ("quant", C.c_int32),
+                ("status", C.c_void_p)]
 
 
 _lib = None
@@ -72,6 +73,8 @@ _SIGNATURES = {
     "medusa_pack_weight": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
                                      C.c_int64, C.c_void_p]),
     "medusa_kv_bytes": (C.c_int64, [C.POINTER(KvDesc)]),
+    "medusa_kv_init": (C.c_int, [C.POINTER(KvDesc), C.c_void_p]),
+    "medusa_test_force_unfused_rope": (C.c_int, [C.c_int]),
     "medusa_kv_write": (C.c_int, [C.POINTER(KvDesc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                   C.c_void_p]),
     "medusa_kv_read": (C.c_int, [C.POINTER(KvDesc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -204,6 +207,18 @@ def medusa_pack_weight(dtype: int, src: torch.Tensor, dst: torch.Tensor, dst_row
 
 def medusa_kv_bytes(kv: KvDesc) -> int:
     return _check(lib().medusa_kv_bytes(C.byref(kv)))
+
+
+def medusa_kv_init(kv: KvDesc, stream=None) -> None:
+    _check(lib().medusa_kv_init(C.byref(kv), _stream(stream)))
+
+
+def medusa_test_force_unfused_rope(on: bool) -> bool:
+    """Test hook (include/medusa_bench.h): returns the previous setting."""
+    return bool(lib().medusa_test_force_unfused_rope(1 if on else 0))
+
+
+MDZ_STATUS_SEQ_RANGE = 1
 
 
 def medusa_kv_write(kv: KvDesc, layer: int, seq: int, pos0: int, n: int, k_rows, v_rows, stream=None) -> None:

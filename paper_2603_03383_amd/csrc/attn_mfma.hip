@@ -547,11 +547,13 @@ bool attn_mfma_supported(int dtype, int tree, const KvGeom& g) {
 // the Q partial sums, its share of the merge) and saves the blocks it takes off the others, so the best count grows
 // with the square root of the prefix: measured best 1 / 3 / 5 / 8 splits at prefixes 128 / 1K / 4K / 16K.
 static int attn_splits(int B, int n_heads, int max_prefix, bool fused) {
-  static const char* env = getenv("MDZ_ATTN_SPLITS");  // development knob
+#ifdef MDZ_DEV_KNOBS
+  static const char* env = getenv("MDZ_ATTN_SPLITS");  // development builds only
   if (env && atoi(env) > 0) return atoi(env) > 32 ? 32 : atoi(env);
+#endif
   const int pairs = B * n_heads;
   if (fused) {
-    int ps = 256 / pairs - 1;
+    int ps = num_cus() / pairs - 1;
     const int by_len = (int)sqrtf((float)(max_prefix >> 5) / 8.0f);
     if (ps > by_len) ps = by_len;
     if (ps > 31) ps = 31;
@@ -581,12 +583,7 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
   // the merge buffer [4][128][32 NU + 2] + [4][2][32 NU] floats overlays the staged Q tile
   constexpr int lds_bytes = 4 * kHD * (32 * NU + 2) * 4 + 4 * 2 * 32 * NU * 4;
   static_assert(lds_bytes >= 32 * NU * kQRow && lds_bytes * (3 - NU) <= 160 * 1024, "LDS budget of the tree kernel");
-  static bool attr_set = false;
-  if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_tree_mfma_kernel<E, Q8, NU>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-    attr_set = true;
-  }
+  MDZ_SET_LDS_ONCE((attn_tree_mfma_kernel<E, Q8, NU>), lds_bytes);
   const int nq = q_heads(g);
   const int splits = attn_splits(B, nq, max_prefix, qkv != nullptr);
   MDZ_REQUIRE(scratch_bytes >= attn_mfma_scratch_bytes(B, nq, max_prefix), MDZ_EWORKSPACE,
@@ -611,8 +608,11 @@ int launch_attention_mfma(int dtype, int tree, const void* q, const Partials* qk
   // 32 queries per workgroup (two workgroups per CU) where the kernel's time is its fixed chain and the machine has
   // room for twice the workgroups; 64 where K and V are long enough that passing them through the CUs twice costs
   // more (measured crossover: between 3K and 4K keys for 16-bit rows, between 12K and 16K for 8-bit rows).
-  static const char* env = getenv("MDZ_ATTN_HALVES");  // development knob: 1 = 32 queries per workgroup, 0 = 64
-  const bool halves = env ? atoi(env) != 0 : (B * q_heads(g) <= 256 && max_prefix < (g.quant ? 14336 : 3584));
+  bool halves = B * q_heads(g) <= num_cus() && max_prefix < (g.quant ? 14336 : 3584);
+#ifdef MDZ_DEV_KNOBS
+  static const char* env = getenv("MDZ_ATTN_HALVES");  // development builds only: 1 = 32 queries per workgroup, 0 = 64
+  if (env) halves = atoi(env) != 0;
+#endif
 #define MDZ_ATTN_CASE(Q8, NU)                                                                                          \
   MDZ_WITH_ELEM16(dtype, return (launch_attention_mfma_t<E, Q8, NU>(tree, q, qkv, cs, g, kc, vc, layer, seq_len, B,    \
                                                                     max_prefix, att_out, scratch, scratch_bytes, st)))

@@ -5,7 +5,10 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "../../include/medusa.h"
+#include "../../include/medusa_bench.h"
 #include "tree_tables.h"
 
 namespace mdz {
@@ -27,6 +30,23 @@ void set_error(const char* fmt, ...);
     if (e_ != hipSuccess) MDZ_FAIL(MDZ_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 #define MDZ_LAUNCH_CHECK() MDZ_HIP(hipGetLastError())
+
+// ---- device facts --------------------------------------------------------------------------------
+// Compute units of the current device (read once; 256 when no device can be asked: host-only plan introspection).
+int num_cus();
+
+// Sets a kernel's dynamic-LDS limit once per process from whichever thread gets there first (calls on different
+// streams may come from different threads).  `flag` is a function-local static std::once_flag of the call site.
+#define MDZ_SET_LDS_ONCE(kernel_expr, bytes)                                                                   \
+  do {                                                                                                         \
+    static std::once_flag once_;                                                                               \
+    static hipError_t once_err_ = hipSuccess;                                                                  \
+    std::call_once(once_, [&]() {                                                                              \
+      once_err_ = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_expr),                              \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (bytes));                    \
+    });                                                                                                        \
+    if (once_err_ != hipSuccess) MDZ_FAIL(MDZ_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(once_err_)); \
+  } while (0)
 
 // ---- element types -----------------------------------------------------------------------------
 struct bf16_t {

@@ -139,13 +139,15 @@ int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const voi
 
 // One thread per (row, i): angle evaluated in double so that long prefixes keep full fp32 accuracy.
 __global__ void rope_table_kernel(int tree, const int32_t* __restrict__ seq_len, int B, int max_prefix, int half,
-                                  double log2_base, float* __restrict__ cs) {
+                                  double log2_base, float* __restrict__ cs, int32_t* status) {
   const TreeTables& t = c_trees[tree];
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= B * t.T * half) return;
   int i = idx % half;
   int n = (idx / half) % t.T;
   int b = idx / (half * t.T);
+  // this kernel opens every verify pass: it reports a length the pass has to clamp
+  if (status && i == 0 && n == 0 && (seq_len[b] < 0 || seq_len[b] > max_prefix)) atomicOr(status, MDZ_STATUS_SEQ_RANGE);
   int S = min(max(seq_len[b], 0), max_prefix);
   double pos = (double)(S + t.depth[n]);
   double ang = pos * exp2(-(double)i / (double)half * log2_base);
@@ -154,14 +156,14 @@ __global__ void rope_table_kernel(int tree, const int32_t* __restrict__ seq_len,
 }
 
 int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
-                      float* cs, hipStream_t st) {
+                      float* cs, int32_t* status, hipStream_t st) {
   ProfScope prof_(PROF_ROPE, st);
   const TreeTables* t = host_tree(tree);
   int half = head_dim / 2;
   int total = B * t->T * half;
   if (total == 0) return MDZ_OK;
   rope_table_kernel<<<(total + 255) / 256, 256, 0, st>>>(tree, seq_len, B, max_prefix, half,
-                                                         log2((double)rope_base), cs);
+                                                         log2((double)rope_base), cs, status);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

@@ -199,7 +199,7 @@ LargePlan plan_large(int M, int N, int K) {
   p.nb_n = (N + kBN - 1) / kBN;
   p.nb_m = (M + kBM - 1) / kBM;
   const int n_stages = K / kCK;
-  int want = (256 + p.nb_n * p.nb_m - 1) / (p.nb_n * p.nb_m);  // enough workgroups for every CU
+  int want = (num_cus() + p.nb_n * p.nb_m - 1) / (p.nb_n * p.nb_m);  // enough workgroups for every CU
   if (want > 8) want = 8;
   if (want > n_stages) want = n_stages;
   if (want < 1) want = 1;
@@ -223,12 +223,7 @@ static int launch_gemm_large_t(const void* X, const void* Wp, float* P, int M, i
   const LargePlan p = plan_large(M, N, K);
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
-  static bool attr_set = false;
-  if (!attr_set) {
-    MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_large_kernel<E, SWIGLU>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    attr_set = true;
-  }
+  MDZ_SET_LDS_ONCE((gemm_large_kernel<E, SWIGLU>), kLdsBytes);
   MDZ_REQUIRE(!SWIGLU || (p.ksplit == 1 && N % 64 == 0 && U), MDZ_EUNSUPPORTED, "gemm: fused SwiGLU needs an unsplit launch");
   res->n = p.ksplit;
   res->split_grid = 0;

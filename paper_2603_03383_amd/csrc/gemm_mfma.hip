@@ -255,8 +255,6 @@ struct GemmPlan {
   int slots;  // most partial-sum slots any band receives
 };
 
-constexpr int kNumCU = 256;
-
 static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
   GemmPlan p;
   const int n_tiles = N / 32;
@@ -268,16 +266,21 @@ static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
   p.whole = max_split <= 1;
   p.nt = 1;
   p.wpb = 4;
+  const int kNumCU = num_cus();
   p.grid = kNumCU;
-  static const char* env = getenv("MDZ_GEMM_PLAN");  // development knob: "wpb,nt,grid,ck" (0 = keep default)
+  bool forced = false;
+#ifdef MDZ_DEV_KNOBS
+  static const char* env = getenv("MDZ_GEMM_PLAN");  // development builds only: "wpb,nt,grid,ck" (0 = keep default)
   if (env) {
     int a = 0, b = 0, c = 0, d = 0;
     if (sscanf(env, "%d,%d,%d,%d", &a, &b, &c, &d) == 4) {
       if (a == 2 || a == 4) p.wpb = a;
       if (c > 0) p.grid = c;
       if ((d == 128 || d == 256) && K % d == 0) p.ck = d;
+      forced = true;
     }
   }
+#endif
   const int bands = (n_tiles + p.wpb * p.nt - 1) / (p.wpb * p.nt);
   const int n_stages = K / p.ck;
   const int64_t U = (int64_t)bands * n_stages;
@@ -285,7 +288,7 @@ static GemmPlan plan_gemm(int M, int N, int K, int max_split) {
   // A grid a little under one workgroup per CU whose equal ranges line up with the column bands (a range is a whole
   // number of bands, or a band a whole number of ranges) leaves no range that straddles a band: fewer partial-sum
   // slots for the consumer to add and no flush in mid-stream.
-  if (!p.whole && !env) {
+  if (!p.whole && !forced) {
     for (int gsz = kNumCU; gsz >= kNumCU * 3 / 4; --gsz) {
       if (U % gsz) continue;
       const int64_t u = U / gsz;
@@ -357,12 +360,7 @@ static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, in
 #define MDZ_GEMM_CASE(WPB, NT, MT, CK)                                                                       \
   if (p.wpb == WPB && p.nt == NT && p.mt == MT && p.ck == CK) {                                              \
     constexpr int lds_bytes = 2 * MT * 32 * (CK * 2 + 16);                                                   \
-    static bool attr_set = false;                                                                            \
-    if (!attr_set) {                                                                                         \
-      MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<WPB, NT, MT, CK, E>),       \
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));                   \
-      attr_set = true;                                                                                       \
-    }                                                                                                        \
+    MDZ_SET_LDS_ONCE((gemm_mfma_kernel<WPB, NT, MT, CK, E>), lds_bytes);                                     \
     gemm_mfma_kernel<WPB, NT, MT, CK, E><<<p.grid, WPB * 64, lds_bytes, st>>>(x, M, K, w, n_tiles, n_stages, P, \
                                                                               ldp, part_stride, p.whole);      \
   } else
@@ -383,26 +381,21 @@ static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, in
 // it is taken only where the bands nearly fill the chip (or fill it a whole number of times).
 bool gemm_mfma_swiglu_supported(int dtype, int M, int N, int K) {
   if (!gemm_mfma_supported(dtype, M, N, K) || N % 128 != 0) return false;
-  const int bands = N / 128;
+  const int bands = N / 128, kNumCU = num_cus();
   return (bands >= kNumCU * 5 / 8 && bands <= kNumCU) || (bands > kNumCU && bands % kNumCU == 0);
 }
 
 template <typename E>
 static int launch_gemm_mfma_swiglu_t(const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {
   ProfScope prof_(M <= 32 ? PROF_GEMM_W32 : PROF_GEMM_W64, st);
-  const int n_tiles = N / 32, n_stages = K / 128, bands = N / 128;
+  const int n_tiles = N / 32, n_stages = K / 128, bands = N / 128, kNumCU = num_cus();
   const int grid = bands < kNumCU ? bands : kNumCU;
   MDZ_REQUIRE((int64_t)bands * n_stages * grid < (int64_t)1 << 31 && (int64_t)M * N < (int64_t)1 << 31, MDZ_ESHAPE,
               "gemm: %d x %d units overflow", bands, n_stages);
 #define MDZ_SWIGLU_CASE(MT)                                                                                         \
   {                                                                                                                  \
     constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 2 * MT * 32 * 33 * 4;                                   \
-    static bool attr_set = false;                                                                                    \
-    if (!attr_set) {                                                                                                 \
-      MDZ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_mfma_kernel<4, 1, MT, 128, E, true>),           \
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));                           \
-      attr_set = true;                                                                                               \
-    }                                                                                                                \
+    MDZ_SET_LDS_ONCE((gemm_mfma_kernel<4, 1, MT, 128, E, true>), lds_bytes);                                         \
     gemm_mfma_kernel<4, 1, MT, 128, E, true><<<grid, 256, lds_bytes, st>>>((const E*)X, M, K, (const E*)Wp, n_tiles, \
                                                                            n_stages, nullptr, 0, 0, 1, (E*)U);       \
   }

@@ -37,9 +37,12 @@ int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
                        int64_t tile_offset, int64_t tile_stride, hipStream_t st);
 int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n,
                    void* k_rows, void* v_rows, bool to_cache, hipStream_t st);
+// status (nullable): device word that receives MDZ_STATUS_SEQ_RANGE when a length arrives out of range
 int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, const int32_t* acc_nodes,
                       const int32_t* accept_len, int32_t* seq_len, int32_t* kv_src_slots, int B,
-                      int max_prefix, hipStream_t st);
+                      int max_prefix, int32_t* status, hipStream_t st);
+// zero fill by a kernel (bytes: any count; p 4-byte aligned)
+int launch_fill_zero(void* p, int64_t bytes, hipStream_t st);
 
 // ---- elementwise / small kernels (elementwise.hip) -------------------------------------------------
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
@@ -50,7 +53,7 @@ int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const voi
                             float eps, hipStream_t st);
 // cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32
 int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
-                      float* cs, hipStream_t st);
+                      float* cs, int32_t* status, hipStream_t st);
 // rotates q and k of qkv [B*T][3d] fp32 (given as partials); q -> q_out [B*T][d] storage dtype; k,v -> cache
 // slots S_b + n
 int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* cs, void* q_out, const KvGeom& g,

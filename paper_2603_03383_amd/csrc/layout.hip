@@ -118,10 +118,11 @@ __global__ void kv_compact_kernel(KvGeom g, T* kc, T* vc, int tree, const int32_
 
 __global__ void kv_compact_finish_kernel(int tree, const int32_t* __restrict__ acc_nodes,
                                          const int32_t* __restrict__ accept_len, int32_t* seq_len,
-                                         int32_t* kv_src_slots, int B, int max_prefix) {
+                                         int32_t* kv_src_slots, int B, int max_prefix, int32_t* status) {
   const TreeTables& t = c_trees[tree];
   int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  if (status && (seq_len[b] < 0 || seq_len[b] > max_prefix)) atomicOr(status, MDZ_STATUS_SEQ_RANGE);
   int S = min(max(seq_len[b], 0), max_prefix);
   int A = min(max(accept_len[b], 0), t.K + 1);
   for (int j = 0; j <= t.K; ++j) {
@@ -131,9 +132,32 @@ __global__ void kv_compact_finish_kernel(int tree, const int32_t* __restrict__ a
   seq_len[b] = S + A;
 }
 
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t* __restrict__ p, int64_t n_words) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n_words; i += stride) {
+    if (i + 4 <= n_words && (reinterpret_cast<uintptr_t>(p) & 15) == 0)
+      *reinterpret_cast<u32x4_t*>(p + i) = u32x4_t{0, 0, 0, 0};
+    else
+      for (int64_t j = i; j < n_words && j < i + 4; ++j) p[j] = 0;
+  }
+}
+
+int launch_fill_zero(void* p, int64_t bytes, hipStream_t st) {
+  MDZ_REQUIRE(p && bytes >= 0 && bytes % 4 == 0 && (reinterpret_cast<uintptr_t>(p) & 3) == 0, MDZ_EINVAL,
+              "fill: needs a 4-byte aligned range");
+  if (bytes == 0) return MDZ_OK;
+  const int64_t words = bytes / 4;
+  int64_t blocks = (words / 4 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  fill_zero_kernel<<<(unsigned)blocks, 256, 0, st>>>((uint32_t*)p, words);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
 int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, const int32_t* acc_nodes,
                       const int32_t* accept_len, int32_t* seq_len, int32_t* kv_src_slots, int B, int max_prefix,
-                      hipStream_t st) {
+                      int32_t* status, hipStream_t st) {
   ProfScope prof_(PROF_COMPACT, st);
   if (B == 0) return MDZ_OK;
   int64_t cols = (int64_t)g.n_layers * g.n_heads * g.head_dim;
@@ -150,7 +174,7 @@ int launch_kv_compact(int dtype, const KvGeom& g, void* kc, void* vc, int tree, 
                                                        seq_len, max_prefix);
   MDZ_LAUNCH_CHECK();
   kv_compact_finish_kernel<<<(B + 63) / 64, 64, 0, st>>>(tree, acc_nodes, accept_len, seq_len, kv_src_slots, B,
-                                                         max_prefix);
+                                                         max_prefix, status);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

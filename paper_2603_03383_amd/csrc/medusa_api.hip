@@ -3,11 +3,29 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "kernels.h"
 
 namespace mdz {
 
 static thread_local char g_err[512] = "";
+
+int num_cus() {
+  static std::once_flag once;
+  static int n = 256;
+  std::call_once(once, []() {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      n = prop.multiProcessorCount;
+    else
+      (void)hipGetLastError();  // no device: host-only callers keep the MI355X count
+  });
+  return n;
+}
+
+static std::atomic<int> g_force_unfused_rope{0};  // set only through medusa_test_force_unfused_rope
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -104,7 +122,7 @@ int launch_tree_attention(int dtype, int tree, const void* q, const KvGeom& g, c
 int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float* cs, void* q_scratch, const KvGeom& g,
                           void* kc, void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                           void* scratch, int64_t scratch_bytes, hipStream_t st) {
-  static const bool unfused = getenv("MDZ_UNFUSED_ROPE") != nullptr;  // development knob
+  const bool unfused = g_force_unfused_rope.load(std::memory_order_relaxed) != 0;
   if (!unfused && attn_mfma_supported(dtype, tree, g) && qkv.stride % 4 == 0 && qkv.ld % 4 == 0 &&
       (qkv.split_grid == 0 || qkv.band_cols % 128 == 0))
     return launch_attention_mfma(dtype, tree, nullptr, &qkv, cs, g, kc, vc, layer, seq_len, B, max_prefix, att_out, scratch,
@@ -126,7 +144,8 @@ struct Workspace {
 
 static int64_t align256(int64_t v) { return (v + 255) & ~int64_t(255); }
 
-static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
+// layer_only: what tree_verify_layer touches (no logits, no head buffers, no selection lists)
+static Workspace carve(const mdz_model_desc& m, int B, int max_prefix, bool layer_only = false) {
   const TreeTables* t = host_tree(m.tree);
   const int64_t es = elem_bytes(m.dtype);
   const int64_t rows = (int64_t)B * t->T;
@@ -147,21 +166,22 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix) {
       int64_t e = gemm_part_elems(m.dtype, (int)rows, sh[0], sh[1]) * 4;
       layer_part = e > layer_part ? e : layer_part;
     }
-    int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d) * 4 * (t->K > 0 ? t->K : 1);  // every head's sums at once
+    int64_t head_part = layer_only ? 0 : gemm_part_elems(m.dtype, B, m.d, m.d) * 4 * (t->K > 0 ? t->K : 1);  // every head's sums at once
     w.part = take(layer_part > head_part ? layer_part : head_part);
   }
   w.q = take(rows * m.d * es);
   w.att = take(rows * m.d * es);
   w.u = take(rows * m.ffn * es);
-  w.logits = take(rows * (int64_t)m.vocab * 4);
-  w.h = take((int64_t)B * m.d * es);
-  w.z = take((int64_t)B * m.d * es * (t->K > 0 ? t->K : 1));
-  w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
-  {  // candidate lists of the selection kernels: the verify step's rows, or the heads' B * (K + 1) rows
+  if (!layer_only) {
+    w.logits = take(rows * (int64_t)m.vocab * 4);
+    w.h = take((int64_t)B * m.d * es);
+    w.z = take((int64_t)B * m.d * es * (t->K > 0 ? t->K : 1));
+    w.hlogits = take((int64_t)B * (t->K + 1) * m.vocab * 4);
+    // candidate lists of the selection kernels: the verify step's rows, or the heads' B * (K + 1) rows
     const int64_t head_rows = (int64_t)B * (t->K + 1);
     w.sel_bytes = topk_scratch_bytes((int)(rows > head_rows ? rows : head_rows));
+    w.sel = take(w.sel_bytes);
   }
-  w.sel = take(w.sel_bytes);
   KvGeom g{m.n_layers, B, kv_heads(m), m.head_dim, max_prefix + t->T, (is_16bit(m.dtype) && m.head_dim % 32 == 0) ? 1 : 0,
            m.n_heads / kv_heads(m), 0};
   w.attn_scratch = take(tree_attention_scratch_bytes(m.dtype, m.tree, g, B, max_prefix));
@@ -356,6 +376,19 @@ int64_t medusa_kv_bytes(const mdz_kv_desc* kv) {
   return kv_elems(geom(kv)) * elem_bytes(kv->dtype);
 }
 
+int medusa_kv_init(const mdz_kv_desc* kv, void* stream) {
+  int rc = check_kv(nullptr, kv, 0, 0);
+  if (rc) return rc;
+  const int64_t bytes = medusa_kv_bytes(kv);
+  if (bytes < 0) return (int)bytes;
+  if ((rc = launch_fill_zero(kv->k, bytes, (hipStream_t)stream))) return rc;
+  if ((rc = launch_fill_zero(kv->v, bytes, (hipStream_t)stream))) return rc;
+  if (kv->status) return launch_fill_zero(kv->status, 4, (hipStream_t)stream);
+  return MDZ_OK;
+}
+
+int medusa_test_force_unfused_rope(int on) { return g_force_unfused_rope.exchange(on ? 1 : 0); }
+
 static int kv_rw(const mdz_kv_desc* kv, int layer, int seq, int pos0, int n, void* k_rows, void* v_rows, bool to_cache,
                  void* stream) {
   int rc = check_kv(nullptr, kv, 0, 0);
@@ -449,32 +482,48 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   return launch_tree_tokens(m.tree, cand_flat, tree_tokens, B, st);
 }
 
-int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
-                      const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* ws, int64_t ws_bytes,
-                      void* stream) {
+// shared by the two layer entry points: argument checks, then the launches over workspace `ws` carved as `L`
+static int verify_layer_checked(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                                const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix) {
   int rc = check_model(model);
   if (rc) return rc;
   if ((rc = check_layer_weights(lw))) return rc;
   if ((rc = check_kv(model, kv, B, max_prefix))) return rc;
   const TreeTables* t = host_tree(model->tree);
-  MDZ_REQUIRE(x_inout && seq_len && ws, MDZ_EINVAL, "tree_verify_layer: NULL pointer");
+  MDZ_REQUIRE(x_inout && seq_len, MDZ_EINVAL, "tree_verify_layer: NULL pointer");
   MDZ_REQUIRE(layer >= 0 && layer < kv->n_layers, MDZ_EINVAL, "tree_verify_layer: layer %d outside the cache's %d",
               layer, kv->n_layers);
   MDZ_REQUIRE(max_prefix + t->T <= kv->cap, MDZ_ESHAPE, "max_prefix %d + T %d exceeds kv cap %d", max_prefix, t->T,
               kv->cap);
+  return MDZ_OK;
+}
+
+static int verify_layer_run(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                            const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, char* ws,
+                            const Workspace& L, hipStream_t st) {
+  int rc;
+  const TreeTables* t = host_tree(model->tree);
+  if ((rc = launch_rope_table(model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
+                              (float*)(ws + L.rope_cs), kv->status, st)))
+    return rc;
+  const int rows = B * t->T;
+  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, single_slot(nullptr, 0, 0), lw->g_attn, ws + L.xn, rows,
+                                    model->d, model->rms_eps, st)))
+    return rc;
+  return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, ws, L, nullptr, nullptr, st);
+}
+
+int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                      const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* ws, int64_t ws_bytes,
+                      void* stream) {
+  int rc = verify_layer_checked(model, lw, layer, x_inout, kv, seq_len, B, max_prefix);
+  if (rc) return rc;
+  MDZ_REQUIRE(ws, MDZ_EINVAL, "tree_verify_layer: NULL workspace");
   const Workspace L = carve(*model, B, max_prefix);
   MDZ_REQUIRE(ws_bytes >= L.total, MDZ_EWORKSPACE, "tree_verify_layer: workspace %lld < %lld bytes",
               (long long)ws_bytes, (long long)L.total);
   if (B == 0) return MDZ_OK;
-  hipStream_t st = (hipStream_t)stream;
-  if ((rc = launch_rope_table(model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
-                              (float*)((char*)ws + L.rope_cs), st)))
-    return rc;
-  const int rows = B * t->T;
-  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, single_slot(nullptr, 0, 0), lw->g_attn, (char*)ws + L.xn, rows,
-                                    model->d, model->rms_eps, st)))
-    return rc;
-  return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, nullptr, nullptr, st);
+  return verify_layer_run(model, lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, (hipStream_t)stream);
 }
 
 int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const int32_t* tree_tokens,
@@ -499,7 +548,8 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   char* wsb = (char*)ws;
   const int rows = B * t->T;
   float* x = (float*)(wsb + L.x);
-  if ((rc = launch_rope_table(m.tree, seq_len, B, max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs), st)))
+  if ((rc = launch_rope_table(m.tree, seq_len, B, max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs),
+                              kv->status, st)))
     return rc;
   if ((rc = launch_embed(m.dtype, w->embed, tree_tokens, x, rows, m.d, m.vocab, st))) return rc;
   void* xn = wsb + L.xn;
@@ -541,7 +591,7 @@ int kv_compact(const mdz_kv_desc* kv, int tree, const int32_t* acc_nodes, const 
   MDZ_REQUIRE(max_prefix + t->T <= kv->cap, MDZ_ESHAPE, "max_prefix %d + T %d exceeds kv cap %d", max_prefix, t->T,
               kv->cap);
   return launch_kv_compact(kv->dtype, geom(kv), kv->k, kv->v, tree, acc_nodes, accept_len, seq_len_inout, kv_src_slots,
-                           B, max_prefix, (hipStream_t)stream);
+                           B, max_prefix, kv->status, (hipStream_t)stream);
 }
 
 #pragma GCC visibility pop

@@ -137,12 +137,20 @@ class DeviceKV:
         d = model.desc
         self.model = model
         self.desc = B.KvDesc(None, None, n_layers or d.n_layers, batch, model.kv_heads, d.head_dim, cap, model.dtype,
-                             B.KV_QUANT[quant])
+                             B.KV_QUANT[quant], None)
         nbytes = B.medusa_kv_bytes(self.desc)
-        self.k = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
-        self.v = torch.zeros(nbytes, dtype=torch.uint8, device=model.device)
-        self.desc.k, self.desc.v = self.k.data_ptr(), self.v.data_ptr()
+        self.k = torch.empty(nbytes, dtype=torch.uint8, device=model.device)
+        self.v = torch.empty(nbytes, dtype=torch.uint8, device=model.device)
+        self.status = torch.empty(1, dtype=torch.int32, device=model.device)
+        self.desc.k, self.desc.v, self.desc.status = self.k.data_ptr(), self.v.data_ptr(), self.status.data_ptr()
         self.bytes = 2 * nbytes
+        B.medusa_kv_init(self.desc)                 # the library zero-fills its own layout (and the status word)
+
+    def check_status(self) -> None:
+        """Synchronises and raises if a kernel had to clamp a sequence length (see MDZ_STATUS_SEQ_RANGE)."""
+        st = int(self.status.item())
+        if st & B.MDZ_STATUS_SEQ_RANGE:
+            raise B.MedusaError(-2, "a sequence length outside [0, max_prefix] reached the kernels and was clamped")
 
     def write(self, layer: int, seq: int, pos0: int, k_rows: torch.Tensor, v_rows: torch.Tensor) -> None:
         """k_rows, v_rows: [key/value heads, n, head_dim] storage dtype."""
@@ -263,3 +271,7 @@ class ChainedDecoder:
             tokens[i].copy_(b.acc_tokens)
             lens[i].copy_(b.accept_len)
         return tokens, lens
+
+    def check_status(self) -> None:
+        """After the caller has synchronised: raises if any step ran with a length beyond max_prefix."""
+        self.kv.check_status()

@@ -675,3 +675,29 @@ def test_cfg5_full_depth_32_layers_ragged_batch():
             k, v = kv.read(l, b, S, 1)
             assert np.abs(U.to_np(k) - kr[:, :1]).max() <= tol * _scale(kr)
             assert np.abs(U.to_np(v) - vr[:, :1]).max() <= tol * _scale(vr)
+
+
+def test_sequence_length_beyond_max_prefix_sets_the_status_word():
+    """Lengths live on the device; one beyond max_prefix cannot be refused by the call, so the kernels clamp it (every
+    access stays inside the cache) and report it through the cache's status word."""
+    w = W.CONFIGS["cfg1_tiny_fp32"]
+    dm = G.device_model(w)
+    T = w.tree.n_nodes
+    kv = P.DeviceKV(dm, batch=2, cap=64 + T)
+    buf = P.StepBuffers(dm, 2, 64)
+    seq_len = _i32([64, 10])
+    P.run_step(dm, kv, buf, None, None, None, seq_len, with_heads=False)
+    torch.cuda.synchronize()
+    assert int(kv.status.item()) == 0
+    kv.check_status()
+    seq_len.copy_(_i32([65, 10]))                     # one past the bound the call was given
+    P.tree_verify_step(dm.desc, dm.weights, buf.tree_tokens, kv.desc, seq_len, 2, 64, buf.node_argmax, None, None, buf.ws)
+    torch.cuda.synchronize()
+    assert int(kv.status.item()) & P.MDZ_STATUS_SEQ_RANGE
+    with pytest.raises(P.MedusaError):
+        kv.check_status()
+    kv.status.zero_()
+    seq_len.copy_(_i32([-3, 10]))
+    P.kv_compact(kv.desc, dm.tree, buf.acc_nodes, buf.accept_len, seq_len, buf.kv_src_slots, 2, 64)
+    torch.cuda.synchronize()
+    assert int(kv.status.item()) & P.MDZ_STATUS_SEQ_RANGE

@@ -1,8 +1,9 @@
 """The tree attention normally starts from the QKV GEMM's partial sums (reduce + RoPE + cache write in its prologue).
 The library also keeps the unfused order of the same steps (a RoPE + cache-write kernel, then the attention kernel on
-rotated queries), which it falls back to when the partial sums do not come in 128-column bands.  A development switch
-read once per process selects it, so these cases run the same layer parity checks in one child process with the
-switch set: ragged and empty prefixes, both query-per-workgroup variants, 16-bit and 8-bit cache rows."""
+rotated queries), which it falls back to when the partial sums do not come in 128-column bands.  A test hook of the
+library (include/medusa_bench.h) forces that order, so these cases run the same layer parity checks with the hook
+set: ragged and empty prefixes, both query-per-workgroup variants, 16-bit and 8-bit cache rows.  They run in a child
+process so that the process-global hook can never leak into other tests."""
 import os
 import subprocess
 import sys
@@ -16,6 +17,7 @@ import sys
 sys.path.insert(0, {root!r})
 import paper_2603_03383_amd as P
 from tests import test_gpu_parity as TP, test_gpu_kv8 as TK
+assert P.medusa_test_force_unfused_rope(True) is False
 P.medusa_profile_begin(64)
 TP.test_small_bf16_layer_ragged_and_empty_prefix([77], 100)
 prof = P.medusa_profile_end()
@@ -33,8 +35,7 @@ print("8-bit rows ok", flush=True)
 
 @pytest.mark.gpu
 def test_layer_parity_with_the_unfused_rope_and_cache_write():
-    env = dict(os.environ, MDZ_UNFUSED_ROPE="1")
-    r = subprocess.run([sys.executable, "-u", "-c", CHILD.format(root=ROOT)], env=env, cwd=ROOT, capture_output=True,
+    r = subprocess.run([sys.executable, "-u", "-c", CHILD.format(root=ROOT)], cwd=ROOT, capture_output=True,
                        text=True, timeout=600)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
     assert "unfused path taken" in r.stdout and "8-bit rows ok" in r.stdout
