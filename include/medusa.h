@@ -200,6 +200,18 @@ int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, 
                       const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* ws,
                       int64_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or carry a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): tree_verify_layer with the library's own scratch, a fixed buffer of
+ * tree_verify_layer_static_scratch_bytes() bytes that is part of the loaded code object (one per GPU, held until the
+ * process ends).  Same arguments, same kernels and bit-identical results as tree_verify_layer; the call allocates and
+ * frees nothing (its first call on a device looks up the buffer's address).  A shape whose scratch need exceeds the
+ * buffer (about 64 tree rows x 7B-class widths at prefixes up to 16K fits; batches do not) is refused with
+ * MDZ_EWORKSPACE and nothing is enqueued.  Every call on a GPU shares that GPU's buffer: calls whose execution can
+ * overlap on one GPU (different streams) race; calls on one stream are safe. */
+int64_t tree_verify_layer_static_scratch_bytes(void);
+int tree_verify_layer_static(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                             const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* stream);
+
 /* Section 3.2, the whole pass: embedding gather of tree_tokens [B, T] -> every layer as above -> final
  * RMSNorm -> LM head -> per-node argmax (ties -> lowest id).  Outputs: node_argmax [B, T];
  * hidden_out (nullable) [B, T, d] storage dtype = the post-final-norm hidden (what medusa_heads reads);

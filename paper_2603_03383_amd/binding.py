@@ -85,6 +85,9 @@ _SIGNATURES = {
     "tree_verify_layer": (C.c_int, [C.POINTER(ModelDesc), C.POINTER(LayerWeights), C.c_int, C.c_void_p,
                                     C.POINTER(KvDesc), C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64,
                                     C.c_void_p]),
+    "tree_verify_layer_static_scratch_bytes": (C.c_int64, []),
+    "tree_verify_layer_static": (C.c_int, [C.POINTER(ModelDesc), C.POINTER(LayerWeights), C.c_int, C.c_void_p,
+                                           C.POINTER(KvDesc), C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "tree_verify_step": (C.c_int, [C.POINTER(ModelDesc), C.POINTER(Weights), C.c_void_p, C.POINTER(KvDesc), C.c_void_p,
                                    C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                    C.c_void_p]),
@@ -248,6 +251,16 @@ def tree_verify_layer(model: ModelDesc, lw: LayerWeights, layer: int, x_inout, k
                       max_prefix: int, ws, stream=None) -> None:
     _check(lib().tree_verify_layer(C.byref(model), C.byref(lw), layer, _ptr(x_inout), C.byref(kv), _ptr(seq_len), B,
                                    max_prefix, _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def tree_verify_layer_static_scratch_bytes() -> int:
+    return int(lib().tree_verify_layer_static_scratch_bytes())
+
+
+def tree_verify_layer_static(model: ModelDesc, lw: LayerWeights, layer: int, x_inout, kv: KvDesc, seq_len, B: int,
+                             max_prefix: int, stream=None) -> None:
+    _check(lib().tree_verify_layer_static(C.byref(model), C.byref(lw), layer, _ptr(x_inout), C.byref(kv), _ptr(seq_len),
+                                          B, max_prefix, _stream(stream)))
 
 
 def tree_verify_step(model: ModelDesc, w: Weights, tree_tokens, kv: KvDesc, seq_len, B: int, max_prefix: int,

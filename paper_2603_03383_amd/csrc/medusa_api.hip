@@ -281,6 +281,34 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   return launch_residual_rmsnorm(m.dtype, x, pr, g_next, xn_next, rows, m.d, m.rms_eps, st);
 }
 
+// ---- static scratch for the entry point that may not allocate ---------------------------------------
+// Device memory that belongs to the loaded code object: one copy per GPU the library runs on, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call
+// returns for the current device.
+constexpr int64_t kStaticScratchBytes = 48ll << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// address of `scratch` on the current device (looked up on the first call per device)
+static int static_scratch(void** out) {
+  int dev = -1;
+  MDZ_HIP(hipGetDevice(&dev));
+  MDZ_REQUIRE(dev >= 0 && dev < kMaxDevices, MDZ_EUNSUPPORTED, "device ordinal %d beyond the %d the library tracks", dev,
+              kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MDZ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    MDZ_REQUIRE(p != nullptr, MDZ_EHIP, "hipGetSymbolAddress returned no address for the static scratch");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MDZ_OK;
+}
+
 static int check_layer_weights(const mdz_layer_weights* lw) {
   MDZ_REQUIRE(lw && lw->wqkv && lw->wo && lw->wgateup && lw->wdown && lw->g_attn && lw->g_ffn, MDZ_EINVAL,
               "layer weights: NULL pointer");
@@ -523,6 +551,24 @@ int tree_verify_layer(const mdz_model_desc* model, const mdz_layer_weights* lw, 
   MDZ_REQUIRE(ws_bytes >= L.total, MDZ_EWORKSPACE, "tree_verify_layer: workspace %lld < %lld bytes",
               (long long)ws_bytes, (long long)L.total);
   if (B == 0) return MDZ_OK;
+  return verify_layer_run(model, lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, (hipStream_t)stream);
+}
+
+int64_t tree_verify_layer_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int tree_verify_layer_static(const mdz_model_desc* model, const mdz_layer_weights* lw, int layer, float* x_inout,
+                             const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, void* stream) {
+  int rc = verify_layer_checked(model, lw, layer, x_inout, kv, seq_len, B, max_prefix);
+  if (rc) return rc;
+  const Workspace L = carve(*model, B, max_prefix, /*layer_only=*/true);
+  MDZ_REQUIRE(L.total <= kStaticScratchBytes, MDZ_EWORKSPACE,
+              "tree_verify_layer_static: this shape (B %d, max_prefix %d) needs %lld bytes of scratch, the built-in buffer "
+              "holds %lld; use tree_verify_layer with a caller workspace",
+              B, max_prefix, (long long)L.total, (long long)kStaticScratchBytes);
+  if (B == 0) return MDZ_OK;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  // every byte of the scratch a kernel reads was written earlier in the same call, so nothing needs clearing
   return verify_layer_run(model, lw, layer, x_inout, kv, seq_len, B, max_prefix, (char*)ws, L, (hipStream_t)stream);
 }
 
