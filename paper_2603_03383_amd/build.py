@@ -48,5 +48,29 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
     return LIB
 
 
+PROBES = os.path.join(HERE, "probes")
+
+
+def build_probes(verbose: bool = True):
+    """Stand-alone measurement programs (probes/*.hip -> probes/<name>): the evidence behind two design decisions,
+    not part of the library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = []
+    for f in sorted(os.listdir(PROBES)):
+        if not f.endswith(".hip"):
+            continue
+        exe = os.path.join(PROBES, f[:-4])
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", os.path.join(PROBES, f), "-o", exe]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {f}:\n{r.stdout}\n{r.stderr}")
+        out.append(exe)
+        if verbose:
+            print(f"built {exe}")
+    return out
+
+
 if __name__ == "__main__":
     build_library()
+    build_probes()
