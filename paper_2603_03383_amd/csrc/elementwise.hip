@@ -52,12 +52,45 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
   return MDZ_OK;
 }
 
+// RoPE table entry idx = (row, i): cos/sin of (S_b + depth[n]) * base^(-2i/hd), the angle evaluated in double so that
+// long prefixes keep full fp32 accuracy.  This opens every verify pass: it also reports a length the pass has to clamp.
+__device__ inline void rope_table_entry(int idx, int tree, const int32_t* __restrict__ seq_len, int B, int max_prefix, int half,
+                                        double log2_base, float* __restrict__ cs, int32_t* status) {
+  const TreeTables& t = c_trees[tree];
+  if (idx >= B * t.T * half) return;
+  int i = idx % half;
+  int n = (idx / half) % t.T;
+  int b = idx / (half * t.T);
+  if (status && i == 0 && n == 0 && (seq_len[b] < 0 || seq_len[b] > max_prefix)) atomicOr(status, MDZ_STATUS_SEQ_RANGE);
+  int S = min(max(seq_len[b], 0), max_prefix);
+  double pos = (double)(S + t.depth[n]);
+  double ang = pos * exp2(-(double)i / (double)half * log2_base);
+  cs[2 * idx] = (float)cos(ang);
+  cs[2 * idx + 1] = (float)sin(ang);
+}
+
+// The RoPE table of a verify pass, computed by extra workgroups of the pass's first norm launch (the two are
+// independent; a launch of its own would cost more than the table takes).  n_blocks == 0: no table in this launch.
+struct RopeJob {
+  const int32_t* seq_len;
+  float* cs;
+  int32_t* status;
+  int tree, B, max_prefix, half, n_blocks;
+  double log2_base;
+};
+
 // x[r] += sum_s P[s][r] (fixed order s = 0..n_part-1), then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g.
 // Either half is optional: P == nullptr skips the residual update, xn == nullptr skips the norm.
+// Workgroups beyond the rows (gridDim.x = rows + rope.n_blocks) fill the RoPE table.
 template <typename T>
 __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict__ x, Partials part,
                                                                const T* __restrict__ g, T* __restrict__ xn, int d,
-                                                               float eps) {
+                                                               float eps, int rows, RopeJob rope) {
+  if ((int)blockIdx.x >= rows) {
+    rope_table_entry((blockIdx.x - rows) * 256 + threadIdx.x, rope.tree, rope.seq_len, rope.B, rope.max_prefix, rope.half,
+                     rope.log2_base, rope.cs, rope.status);
+    return;
+  }
   const float* P = part.p;
   const int64_t part_stride = part.stride, ldp = part.ld;
   __shared__ float red[4];
@@ -84,7 +117,12 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
 template <typename T>
 __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __restrict__ x, Partials part,
                                                                      const T* __restrict__ g, T* __restrict__ xn,
-                                                                     int d, float eps) {
+                                                                     int d, float eps, int rows, RopeJob rope) {
+  if ((int)blockIdx.x >= rows) {
+    rope_table_entry((blockIdx.x - rows) * 1024 + threadIdx.x, rope.tree, rope.seq_len, rope.B, rope.max_prefix, rope.half,
+                     rope.log2_base, rope.cs, rope.status);
+    return;
+  }
   const float* P = part.p;
   const int64_t part_stride = part.stride, ldp = part.ld;
   __shared__ float red[16];
@@ -125,47 +163,34 @@ __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __re
   *reinterpret_cast<Quad<T>*>(xn + (int64_t)r * d + i) = o;
 }
 
-int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
-                            float eps, hipStream_t st) {
+static int launch_norm_with_rope(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
+                                 float eps, RopeJob rope, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
-  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0)
-    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
-  else
-    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_kernel<E><<<rows, 256, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps)));
+  const int entries = rope.n_blocks ? rope.B * host_tree(rope.tree)->T * rope.half : 0;
+  if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0) {
+    rope.n_blocks = (entries + 1023) / 1024;
+    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows + rope.n_blocks, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d,
+                                                                                              eps, rows, rope)));
+  } else {
+    rope.n_blocks = (entries + 255) / 256;
+    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_kernel<E><<<rows + rope.n_blocks, 256, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps,
+                                                                                        rows, rope)));
+  }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }
 
-// One thread per (row, i): angle evaluated in double so that long prefixes keep full fp32 accuracy.
-__global__ void rope_table_kernel(int tree, const int32_t* __restrict__ seq_len, int B, int max_prefix, int half,
-                                  double log2_base, float* __restrict__ cs, int32_t* status) {
-  const TreeTables& t = c_trees[tree];
-  int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= B * t.T * half) return;
-  int i = idx % half;
-  int n = (idx / half) % t.T;
-  int b = idx / (half * t.T);
-  // this kernel opens every verify pass: it reports a length the pass has to clamp
-  if (status && i == 0 && n == 0 && (seq_len[b] < 0 || seq_len[b] > max_prefix)) atomicOr(status, MDZ_STATUS_SEQ_RANGE);
-  int S = min(max(seq_len[b], 0), max_prefix);
-  double pos = (double)(S + t.depth[n]);
-  double ang = pos * exp2(-(double)i / (double)half * log2_base);
-  cs[2 * idx] = (float)cos(ang);
-  cs[2 * idx + 1] = (float)sin(ang);
+int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
+                            float eps, hipStream_t st) {
+  return launch_norm_with_rope(dtype, x, part, g, xn, rows, d, eps, RopeJob{}, st);
 }
 
-int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
-                      float* cs, int32_t* status, hipStream_t st) {
-  ProfScope prof_(PROF_ROPE, st);
-  const TreeTables* t = host_tree(tree);
-  int half = head_dim / 2;
-  int total = B * t->T * half;
-  if (total == 0) return MDZ_OK;
-  rope_table_kernel<<<(total + 255) / 256, 256, 0, st>>>(tree, seq_len, B, max_prefix, half,
-                                                         log2((double)rope_base), cs, status);
-  MDZ_LAUNCH_CHECK();
-  return MDZ_OK;
+int launch_first_norm_and_rope_table(int dtype, float* x, const void* g, void* xn, int rows, int d, float eps, int tree,
+                                     const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base, float* cs,
+                                     int32_t* status, hipStream_t st) {
+  RopeJob rope{seq_len, cs, status, tree, B, max_prefix, head_dim / 2, 1, log2((double)rope_base)};
+  return launch_norm_with_rope(dtype, x, single_slot(nullptr, 0, 0), g, xn, rows, d, eps, rope, st);
 }
 
 // grid (B*T, query heads), block = head_dim/2 threads... generalised: threads stride over i < half.  The QKV GEMM

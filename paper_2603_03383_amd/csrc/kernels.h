@@ -51,9 +51,12 @@ int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, 
 // to the storage dtype (skipped if xn == NULL)
 int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
                             float eps, hipStream_t st);
-// cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32
-int launch_rope_table(int tree, const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base,
-                      float* cs, int32_t* status, hipStream_t st);
+// the first norm of a verify pass (no residual update: xn = RMSNorm(x; g)) and the pass's RoPE table in ONE launch:
+// cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32; status (nullable)
+// receives MDZ_STATUS_SEQ_RANGE when a length arrives out of range
+int launch_first_norm_and_rope_table(int dtype, float* x, const void* g, void* xn, int rows, int d, float eps, int tree,
+                                     const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base, float* cs,
+                                     int32_t* status, hipStream_t st);
 // rotates q and k of qkv [B*T][3d] fp32 (given as partials); q -> q_out [B*T][d] storage dtype; k,v -> cache
 // slots S_b + n
 int launch_rope_kvwrite(int dtype, int tree, const Partials& qkv, const float* cs, void* q_out, const KvGeom& g,

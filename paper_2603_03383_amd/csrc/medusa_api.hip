@@ -531,12 +531,10 @@ static int verify_layer_run(const mdz_model_desc* model, const mdz_layer_weights
                             const Workspace& L, hipStream_t st) {
   int rc;
   const TreeTables* t = host_tree(model->tree);
-  if ((rc = launch_rope_table(model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
-                              (float*)(ws + L.rope_cs), kv->status, st)))
-    return rc;
   const int rows = B * t->T;
-  if ((rc = launch_residual_rmsnorm(model->dtype, x_inout, single_slot(nullptr, 0, 0), lw->g_attn, ws + L.xn, rows,
-                                    model->d, model->rms_eps, st)))
+  if ((rc = launch_first_norm_and_rope_table(model->dtype, x_inout, lw->g_attn, ws + L.xn, rows, model->d, model->rms_eps,
+                                             model->tree, seq_len, B, max_prefix, model->head_dim, model->rope_base,
+                                             (float*)(ws + L.rope_cs), kv->status, st)))
     return rc;
   return run_layer(*model, *lw, layer, x_inout, kv, seq_len, B, max_prefix, ws, L, nullptr, nullptr, st);
 }
@@ -594,14 +592,11 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
   char* wsb = (char*)ws;
   const int rows = B * t->T;
   float* x = (float*)(wsb + L.x);
-  if ((rc = launch_rope_table(m.tree, seq_len, B, max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs),
-                              kv->status, st)))
-    return rc;
   if ((rc = launch_embed(m.dtype, w->embed, tree_tokens, x, rows, m.d, m.vocab, st))) return rc;
   void* xn = wsb + L.xn;
   void* hid = hidden_out ? hidden_out : xn;
-  if ((rc = launch_residual_rmsnorm(m.dtype, x, single_slot(nullptr, 0, 0), w->layers[0].g_attn, xn, rows, m.d,
-                                    m.rms_eps, st)))
+  if ((rc = launch_first_norm_and_rope_table(m.dtype, x, w->layers[0].g_attn, xn, rows, m.d, m.rms_eps, m.tree, seq_len, B,
+                                             max_prefix, m.head_dim, m.rope_base, (float*)(wsb + L.rope_cs), kv->status, st)))
     return rc;
   for (int l = 0; l < m.n_layers; ++l) {
     const bool last = l + 1 == m.n_layers;
