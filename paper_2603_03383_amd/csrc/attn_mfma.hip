@@ -496,39 +496,40 @@ __global__ void __launch_bounds__(256)
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-  constexpr int kTogether = 8;  // up to eight splits: every load is requested before the first is used
-  if (n_splits <= kTogether) {
+  // Splits are taken eight at a time: the loads of a group are all requested before the first is used, so a merge of
+  // many splits costs one memory round trip per eight, not one per split.  The weights refer to the running maximum
+  // of the groups seen so far (the sums are rescaled when a later group raises it), in a fixed order.
+  constexpr int kTogether = 8;
+  for (int s0 = 0; s0 < n_splits; s0 += kTogether) {
     float ms[kTogether], ls[kTogether];
     float4 v0[kTogether], v1[kTogether];
 #pragma unroll
     for (int s = 0; s < kTogether; ++s)
-      if (s < n_splits) {
-        ms[s] = part_ml[((p0 + s) * 2 + 0) * kTQ + qq];
-        ls[s] = part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
-        const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
+      if (s0 + s < n_splits) {
+        ms[s] = part_ml[((p0 + s0 + s) * 2 + 0) * kTQ + qq];
+        ls[s] = part_ml[((p0 + s0 + s) * 2 + 1) * kTQ + qq];
+        const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s0 + s) * kTQ + qq) * kHD + f0);
         v0[s] = po[0], v1[s] = po[1];
       }
+    float Mg = M;
 #pragma unroll
     for (int s = 0; s < kTogether; ++s)
-      if (s < n_splits) M = fmaxf(M, ms[s]);
+      if (s0 + s < n_splits) Mg = fmaxf(Mg, ms[s]);
+    if (Mg != M) {  // (first group: M = -inf and the sums are zero)
+      const float r = M == -INFINITY ? 0.f : fast_exp2(M - Mg);
+      L *= r;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] *= r;
+      M = Mg;
+    }
 #pragma unroll
     for (int s = 0; s < kTogether; ++s)
-      if (s < n_splits) {
+      if (s0 + s < n_splits) {
         const float w = fast_exp2(ms[s] - M);
         L += w * ls[s];
         acc[0] += w * v0[s].x, acc[1] += w * v0[s].y, acc[2] += w * v0[s].z, acc[3] += w * v0[s].w;
         acc[4] += w * v1[s].x, acc[5] += w * v1[s].y, acc[6] += w * v1[s].z, acc[7] += w * v1[s].w;
       }
-  } else {
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((p0 + s) * 2 + 0) * kTQ + qq]);
-    for (int s = 0; s < n_splits; ++s) {
-      const float w = fast_exp2(part_ml[((p0 + s) * 2 + 0) * kTQ + qq] - M);
-      L += w * part_ml[((p0 + s) * 2 + 1) * kTQ + qq];
-      const float4* po = reinterpret_cast<const float4*>(part_o + ((p0 + s) * kTQ + qq) * kHD + f0);
-      const float4 v0 = po[0], v1 = po[1];
-      acc[0] += w * v0.x, acc[1] += w * v0.y, acc[2] += w * v0.z, acc[3] += w * v0.w;
-      acc[4] += w * v1.x, acc[5] += w * v1.y, acc[6] += w * v1.z, acc[7] += w * v1.w;
-    }
   }
   const float inv = 1.0f / L;
   uint32_t pk[4];

@@ -237,7 +237,8 @@ def test_cfg2_full_size_layer_bf16():
 
 
 @pytest.mark.parametrize("S_list,max_prefix", [([0], 0), ([1], 5), ([77], 100), ([300, 0, 45], 300), ([5000, 131], 5003),
-                                                ([31], 31), ([32], 40), ([33], 33)])
+                                                ([31], 31), ([32], 40), ([33], 33),
+                                                ([40000], 40000)])      # 13 key-splits: the merge kernel's second group
 def test_small_bf16_layer_ragged_and_empty_prefix(S_list, max_prefix):
     w = W.CONFIGS["cfg2_layer_bf16"].with_(d=256, n_heads=2, head_dim=128, ffn=704, name="small_bf16")
     r = _layer_case(w, S_list, max_prefix, x_seed=f"small_x{len(S_list)}")
