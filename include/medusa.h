@@ -89,7 +89,8 @@ typedef struct {
 /* HOST struct.  layers: HOST array of n_layers entries.  embed: [vocab, d] ROW-MAJOR storage dtype
  * (it is gathered, not multiplied).  lm_head: packed [vocab, d].  Medusa head k (0-based here):
  * head_w1[k] packed [d, d], head_b1[k] bias [d] storage dtype or NULL, head_lm[k] packed [vocab, d].
- * head_b1 itself may be NULL (no head has a bias). */
+ * head_b1 itself may be NULL (no head has a bias).  If the packed head_w1 matrices lie back to back in memory
+ * (head_w1[k] == head_w1[0] + k * medusa_packed_bytes(dtype, d, d)) the heads' first layers run as one launch. */
 typedef struct {
   const mdz_layer_weights* layers;
   const void* embed;

@@ -441,19 +441,24 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
   return MDZ_OK;
 }
 
-// blockIdx.y = head: its partial sums start part_head_stride floats after the previous head's, its z rows n elements
+// blockIdx.y = head, its z rows n elements.  part_head_stride >= 0: the heads' first-layer products came from separate
+// GEMMs, head k's partial sums [B][d] start k * part_head_stride floats into the region.  part_head_stride < 0: they
+// came from ONE GEMM over the heads' stacked matrices: head k's pre-activations are columns k*d .. k*d+d-1 of [B][K*d].
 template <typename T>
 __global__ void head_residual_kernel(const T* __restrict__ h, Partials part, int64_t part_head_stride, HeadBiases b1s,
                                      T* __restrict__ z, int64_t n, int d) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n) return;
   const int k = blockIdx.y;
-  const float* pp = part.p + k * part_head_stride;
+  const int j = (int)(idx % d);
   const T* b1 = reinterpret_cast<const T*>(b1s.p[k]);
+  const bool stacked = part_head_stride < 0;
+  const int col = stacked ? k * d + j : j;
+  const float* pp = stacked ? part.p + (idx / d) * part.ld + col : part.p + k * part_head_stride + idx;
   float p = 0.f;
-  const int n_part = part.count((int)(idx % d));
-  for (int s = 0; s < n_part; ++s) p += pp[(int64_t)s * part.stride + idx];
-  p += b1 ? to_float(b1[idx % d]) : 0.f;
+  const int n_part = part.count(col);
+  for (int s = 0; s < n_part; ++s) p += pp[(int64_t)s * part.stride];
+  p += b1 ? to_float(b1[j]) : 0.f;
   z[k * n + idx] = from_float<T>(to_float(h[idx]) + silu_f(p));
 }
 

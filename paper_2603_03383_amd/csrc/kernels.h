@@ -69,7 +69,8 @@ int launch_gather_rows(int dtype, const void* hidden, const int32_t* src_row, in
                        hipStream_t st);
 // z = h + SiLU(pre + b1) -> storage dtype
 // z[k] = h + SiLU(sums of head k + bias of head k) for all n_heads Medusa heads in one launch: the partial sums of
-// head k start part_head_stride floats after those of head k - 1 (same slot layout), z [n_heads][B][d]
+// head k start part_head_stride floats after those of head k - 1 (same slot layout), or, part_head_stride < 0, are
+// columns k*d .. of the [B][n_heads*d] output of one GEMM over the stacked matrices; z [n_heads][B][d]
 struct HeadBiases {
   const void* p[MDZ_MAX_HEADS];
 };

@@ -166,7 +166,12 @@ static Workspace carve(const mdz_model_desc& m, int B, int max_prefix, bool laye
       int64_t e = gemm_part_elems(m.dtype, (int)rows, sh[0], sh[1]) * 4;
       layer_part = e > layer_part ? e : layer_part;
     }
-    int64_t head_part = layer_only ? 0 : gemm_part_elems(m.dtype, B, m.d, m.d) * 4 * (t->K > 0 ? t->K : 1);  // every head's sums at once
+    // every head's first-layer sums at once: from separate GEMMs, or from one GEMM over the stacked matrices
+    int64_t head_part = layer_only ? 0 : gemm_part_elems(m.dtype, B, m.d, m.d) * 4 * (t->K > 0 ? t->K : 1);
+    if (!layer_only && t->K > 1) {
+      const int64_t stacked = gemm_part_elems(m.dtype, B, t->K * m.d, m.d) * 4;
+      head_part = stacked > head_part ? stacked : head_part;
+    }
     w.part = take(layer_part > head_part ? layer_part : head_part);
   }
   w.q = take(rows * m.d * es);
@@ -490,13 +495,24 @@ int medusa_heads(const mdz_model_desc* model, const mdz_weights* w, const void* 
   const int64_t head_part = gemm_part_elems(m.dtype, B, m.d, m.d);
   const int64_t zrow = (int64_t)B * m.d * elem_bytes(m.dtype);
   HeadBiases b1s{};
-  for (int k = 0; k < t->K; ++k) {
-    b1s.p[k] = w->head_b1 ? w->head_b1[k] : nullptr;
-    if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part + k * head_part, B, m.d, m.d, m.d, max_split_for(B), &pr, st)))
-      return rc;
+  for (int k = 0; k < t->K; ++k) b1s.p[k] = w->head_b1 ? w->head_b1[k] : nullptr;
+  // The packed layout puts a matrix's 128-row bands one after the other, so first-layer matrices that lie back to
+  // back in memory ARE the packed [K*d, d] stack of them: one launch then serves all heads (they read the same h).
+  bool stacked = t->K > 1 && m.d % 128 == 0 && (int64_t)B * t->K * m.d < ((int64_t)1 << 31) / 16;
+  const int64_t w1_bytes = medusa_packed_bytes(m.dtype, m.d, m.d);
+  for (int k = 1; k < t->K && stacked; ++k)
+    stacked = (const char*)w->head_w1[k] == (const char*)w->head_w1[0] + k * w1_bytes;
+  if (stacked) {
+    const int n_all = t->K * m.d;
+    if ((rc = launch_gemm(m.dtype, h, w->head_w1[0], part, B, n_all, m.d, n_all, max_split_for(B), &pr, st))) return rc;
+    if ((rc = launch_head_residual(m.dtype, h, pr, -1, b1s, t->K, z, B, m.d, st))) return rc;
+  } else {
+    for (int k = 0; k < t->K; ++k)
+      if ((rc = launch_gemm(m.dtype, h, w->head_w1[k], part + k * head_part, B, m.d, m.d, m.d, max_split_for(B), &pr, st)))
+        return rc;
+    pr.p = part;
+    if ((rc = launch_head_residual(m.dtype, h, pr, head_part, b1s, t->K, z, B, m.d, st))) return rc;
   }
-  pr.p = part;
-  if ((rc = launch_head_residual(m.dtype, h, pr, head_part, b1s, t->K, z, B, m.d, st))) return rc;
   int seg = 1;
   for (int k = 0; k < t->K; ++k) {
     float* lk = hl + (int64_t)(k + 1) * V;

@@ -89,7 +89,22 @@ class DeviceModel:
     def add_medusa_head(self, w1, b1, lm) -> None:
         self._heads.append((self.pack([w1]), None if b1 is None else self._gain(b1), self.pack([lm])))
 
+    def _stack_head_w1(self) -> None:
+        """Moves the heads' packed first-layer matrices into one allocation, back to back: the library then runs them
+        as a single launch (memory plumbing only: byte copies of what medusa_pack_weight wrote)."""
+        if len(self._heads) < 2 or len({h[0].numel() for h in self._heads}) != 1:
+            return
+        n = self._heads[0][0].numel()
+        both = torch.empty(n * len(self._heads), dtype=torch.uint8, device=self.device)
+        for k, (w1, b1, lm) in enumerate(self._heads):
+            both[k * n:(k + 1) * n].copy_(w1)
+            self._keep = [t for t in self._keep if t is not w1]
+            self._heads[k] = (both[k * n:(k + 1) * n], b1, lm)
+        self._keep.append(both)
+        torch.cuda.synchronize(self.device)
+
     def finalize(self) -> "DeviceModel":
+        self._stack_head_w1()
         n = len(self._layers)
         self._layer_arr = (B.LayerWeights * max(n, 1))(*self._layers)
         nh = len(self._heads)

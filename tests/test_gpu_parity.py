@@ -124,6 +124,31 @@ def test_cfg1_heads_verify_accept_compact(cfg1):
         np.testing.assert_allclose(v.cpu().numpy()[:, :S2], vc[l][:, :S2], rtol=0, atol=2e-5)
 
 
+def test_cfg1_heads_with_separately_allocated_first_layers(cfg1, monkeypatch):
+    """The heads' first-layer matrices may be separate allocations (one GEMM launch per head) or lie back to back (one
+    launch for all, what DeviceModel arranges): both orders of work give the oracle's candidates and logits."""
+    w, model, tree = cfg1["w"], cfg1["model"], cfg1["tree"]
+    monkeypatch.setattr(P.DeviceModel, "_stack_head_w1", lambda self: None)
+    dm = G.device_model(w)
+    ptrs = [dm._w1[k] for k in range(tree["K"])]
+    assert any(ptrs[k + 1] - ptrs[k] != P.medusa_packed_bytes(dm.dtype, w.d, w.d) for k in range(tree["K"] - 1))
+    h = cfg1["last_hidden"].astype(np.float32)
+    heads = O.medusa_heads(h, model, tree)
+    buf = P.StepBuffers(dm, 1, cfg1["S"], want_head_logits=True)
+    P.medusa_heads(dm.desc, dm.weights, torch.tensor(h, device=G.DEV).view(1, 1, -1), None, None, 1, 1, buf.cand_flat,
+                   buf.tree_tokens, buf.head_logits, buf.ws)
+    torch.cuda.synchronize()
+    hl = buf.head_logits[0].cpu().numpy()
+    assert np.abs(hl - heads["head_logits"]).max() <= TOL["fp32"] * _scale(heads["head_logits"])
+    assert buf.cand_flat[0].cpu().numpy().tolist() == heads["cand_flat"].tolist()
+    # and the stacked arrangement gives bit-identical logits
+    buf2 = P.StepBuffers(cfg1["dm"], 1, cfg1["S"], want_head_logits=True)
+    P.medusa_heads(cfg1["dm"].desc, cfg1["dm"].weights, torch.tensor(h, device=G.DEV).view(1, 1, -1), None, None, 1, 1,
+                   buf2.cand_flat, buf2.tree_tokens, buf2.head_logits, buf2.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.head_logits, buf2.head_logits) and torch.equal(buf.cand_flat, buf2.cand_flat)
+
+
 @pytest.mark.parametrize("m", [0, 1, 2, 3])
 def test_cfg1_planted_acceptance_and_chained_step(cfg1, m):
     """Tree tokens carry the model's own greedy continuation along one path: A must be m+1, the compacted
