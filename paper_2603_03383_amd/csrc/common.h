@@ -35,17 +35,21 @@ void set_error(const char* fmt, ...);
 // Compute units of the current device (read once; 256 when no device can be asked: host-only plan introspection).
 int num_cus();
 
-// Sets a kernel's dynamic-LDS limit once per process from whichever thread gets there first (calls on different
-// streams may come from different threads).  `flag` is a function-local static std::once_flag of the call site.
+// Sets a kernel's dynamic-LDS limit once per device, from whichever thread gets there first (calls on different
+// streams may come from different threads; a function attribute belongs to the device the code object is loaded on).
+constexpr int kMaxDevices = 64;
 #define MDZ_SET_LDS_ONCE(kernel_expr, bytes)                                                                   \
   do {                                                                                                         \
-    static std::once_flag once_;                                                                               \
-    static hipError_t once_err_ = hipSuccess;                                                                  \
-    std::call_once(once_, [&]() {                                                                              \
-      once_err_ = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_expr),                              \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (bytes));                    \
+    static std::once_flag once_[::mdz::kMaxDevices];                                                           \
+    static hipError_t once_err_[::mdz::kMaxDevices];                                                           \
+    int dev_ = 0;                                                                                              \
+    if (hipGetDevice(&dev_) != hipSuccess || dev_ < 0 || dev_ >= ::mdz::kMaxDevices) dev_ = 0;                 \
+    std::call_once(once_[dev_], [&]() {                                                                        \
+      once_err_[dev_] = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_expr),                        \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (bytes));              \
     });                                                                                                        \
-    if (once_err_ != hipSuccess) MDZ_FAIL(MDZ_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(once_err_)); \
+    if (once_err_[dev_] != hipSuccess)                                                                         \
+      MDZ_FAIL(MDZ_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(once_err_[dev_]));                      \
   } while (0)
 
 // ---- element types -----------------------------------------------------------------------------

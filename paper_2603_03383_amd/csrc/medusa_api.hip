@@ -293,7 +293,6 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
 constexpr int64_t kStaticScratchBytes = 48ll << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-constexpr int kMaxDevices = 64;
 static std::mutex g_scratch_mu;
 static void* g_scratch_ptr[kMaxDevices] = {};
 
