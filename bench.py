@@ -72,7 +72,8 @@ def build_device(w, with_heads):
     import paper_2603_03383_amd as P
     dev = "cuda:0"
     dm = P.DeviceModel(d=w.d, n_heads=w.n_heads, head_dim=w.head_dim, ffn=w.ffn, vocab=w.vocab, n_layers=w.n_layers,
-                       dtype=w.dtype, tree=w.tree.name, n_kv_heads=w.n_kv_heads, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev)
+                       dtype=w.dtype, tree=w.tree.name, n_kv_heads=w.n_kv_heads, rms_eps=w.rms_eps, rope_base=w.rope_base, device=dev,
+                       ffn_f16=w.ffn_f16)
     for l in range(w.n_layers):
         mats = [W.layer_weight(w, l, m, dev) for m in W.LAYER_MATS]
         dm.add_layer(*mats, W.norm_gain(w, f"layer{l}.g_attn", dev), W.norm_gain(w, f"layer{l}.g_ffn", dev))
@@ -307,6 +308,8 @@ def main():
     ap.add_argument("--no-heads", action="store_true", help="time verify+accept+compact only")
     ap.add_argument("--prefix", type=int, default=None, help="override the workload's prefix length (every sequence)")
     ap.add_argument("--kv8", action="store_true", help="8-bit KV cache rows (E4M3 codes + one fp32 scale per row)")
+    ap.add_argument("--ffn-f16", action="store_true",
+                    help="bf16 model with binary16 feed-forward operands (the model descriptor's ffn_f16 option)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-extras", action="store_true",
                     help="leave out the autoregressive baseline, the chained loop and the other configurations "
@@ -324,6 +327,8 @@ def main():
     w = W.CONFIGS[args.workload]
     if args.kv8:
         w = w.with_(name=f"{w.name}+kv8", kv_quant="fp8e4m3")
+    if args.ffn_f16:
+        w = w.with_(name=f"{w.name}+ffn_f16", ffn_f16=True)
     if args.prefix is not None:
         w = w.with_(name=f"{w.name}@prefix{args.prefix}", prefix=(args.prefix,) * w.batch)
     with_heads = not args.no_heads and w.n_layers > 1
@@ -419,7 +424,7 @@ def main():
 
     # configs 2, 4 and 5 on the same weights (default headline run only)
     others = None
-    if args.workload == "cfg3_step_1k" and not (args.skip_extras or args.kv8 or args.no_heads or args.prefix is not None):
+    if args.workload == "cfg3_step_1k" and not (args.skip_extras or args.kv8 or args.ffn_f16 or args.no_heads or args.prefix is not None):
         del kv, buf
         torch.cuda.empty_cache()
         others = other_configs(dm, w, args.steps, args.warmup)

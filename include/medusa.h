@@ -62,7 +62,15 @@ typedef enum { MDZ_KV_PLAIN = 0, MDZ_KV_FP8E4M3 = 1 } mdz_kv_quant;
 
 /* HOST struct: the decoder's shape. d == n_heads * head_dim (no bias).  n_kv_heads: key/value heads of
  * grouped-query attention (Table 1 of the paper: 32 query heads, 8 key/value heads); it must divide n_heads, query
- * head h reads key/value head h / (n_heads / n_kv_heads); 0 means n_heads (plain multi-head attention). */
+ * head h reads key/value head h / (n_heads / n_kv_heads); 0 means n_heads (plain multi-head attention).
+ * ffn_f16 = 1 (bf16 models): the two matrix products of every layer's feed-forward block take IEEE binary16
+ * operands.  The layer's wgateup and wdown must then be packed with medusa_pack_weight_bf16_as_f16 (the same values:
+ * a bf16 number of magnitude in [2^-14, 65504] is a binary16 number), and the block's two activations (the
+ * normalised input, the SwiGLU output) are rounded to 11 significant bits instead of 8, which are the two largest
+ * terms of a deep bf16 stack's rounding error.  What the layer computes (Section 3.2: the ordinary decoder layer on
+ * the tree's rows) is unchanged; every other buffer, the gains, the cache and the other matrices stay bf16.  An
+ * activation beyond 65504 in magnitude would overflow: this is an option for models whose feed-forward activations
+ * are known to stay inside that range, off by default. */
 typedef struct {
   int32_t d, n_heads, head_dim, ffn, vocab, n_layers;
   int32_t dtype; /* mdz_dtype */
@@ -70,6 +78,7 @@ typedef struct {
   float rms_eps;
   float rope_base;
   int32_t n_kv_heads;
+  int32_t ffn_f16; /* 0 or 1; 1 is allowed for MDZ_BF16 only (see below) */
 } mdz_model_desc;
 
 /* HOST struct of device pointers: one decoder layer.  Matrices are in the library's PACKED layout
@@ -153,6 +162,12 @@ int64_t medusa_packed_bytes(int dtype, int64_t n_rows, int64_t k);
  * stride 2).  n_rows must be a multiple of R unless tile_stride == 1 and this is the last matrix. */
 int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
                        int64_t tile_offset, int64_t tile_stride, void* stream);
+
+/* The same re-tiling of a ROW-MAJOR bf16 matrix, with every element converted to IEEE binary16 on the way (exact
+ * for magnitudes in [2^-14, 65504], round-to-nearest-even into binary16's subnormals below, infinity above): the
+ * form of wgateup and wdown that a model with ffn_f16 = 1 takes.  Same sizes and bytes as the bf16 packing. */
+int medusa_pack_weight_bf16_as_f16(const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
+                                   int64_t tile_offset, int64_t tile_stride, void* stream);
 
 /* ---- KV cache ------------------------------------------------------------------------------- */
 

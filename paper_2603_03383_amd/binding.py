@@ -35,7 +35,8 @@ class MedusaError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [("d", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
                 ("vocab", C.c_int32), ("n_layers", C.c_int32), ("dtype", C.c_int32), ("tree", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int32),
+                ("ffn_f16", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -70,6 +71,8 @@ _SIGNATURES = {
     "medusa_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "medusa_pack_tile_rows": (C.c_int, [C.c_int]),
     "medusa_packed_bytes": (C.c_int64, [C.c_int, C.c_int64, C.c_int64]),
+    "medusa_pack_weight_bf16_as_f16": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
+                                                 C.c_int64, C.c_void_p]),
     "medusa_pack_weight": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
                                      C.c_int64, C.c_void_p]),
     "medusa_kv_bytes": (C.c_int64, [C.POINTER(KvDesc)]),
@@ -199,6 +202,13 @@ def medusa_pack_tile_rows(dtype: int) -> int:
 
 def medusa_packed_bytes(dtype: int, n_rows: int, k: int) -> int:
     return _check(lib().medusa_packed_bytes(dtype, n_rows, k))
+
+
+def medusa_pack_weight_bf16_as_f16(src: torch.Tensor, dst: torch.Tensor, dst_rows: int, tile_offset: int = 0,
+                                   tile_stride: int = 1, stream=None) -> None:
+    n_rows, k = src.shape
+    _check(lib().medusa_pack_weight_bf16_as_f16(_ptr(src), n_rows, k, _ptr(dst), dst_rows, tile_offset, tile_stride,
+                                                _stream(stream)))
 
 
 def medusa_pack_weight(dtype: int, src: torch.Tensor, dst: torch.Tensor, dst_rows: int, tile_offset: int = 0,

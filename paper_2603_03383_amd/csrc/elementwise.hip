@@ -82,9 +82,9 @@ struct RopeJob {
 // x[r] += sum_s P[s][r] (fixed order s = 0..n_part-1), then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g.
 // Either half is optional: P == nullptr skips the residual update, xn == nullptr skips the norm.
 // Workgroups beyond the rows (gridDim.x = rows + rope.n_blocks) fill the RoPE table.
-template <typename T>
+template <typename T, typename TO = T>
 __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict__ x, Partials part,
-                                                               const T* __restrict__ g, T* __restrict__ xn, int d,
+                                                               const T* __restrict__ g, TO* __restrict__ xn, int d,
                                                                float eps, int rows, RopeJob rope) {
   if ((int)blockIdx.x >= rows) {
     rope_table_entry((blockIdx.x - rows) * 256 + threadIdx.x, rope.tree, rope.seq_len, rope.B, rope.max_prefix, rope.half,
@@ -109,14 +109,14 @@ __global__ void __launch_bounds__(256) residual_rmsnorm_kernel(float* __restrict
   if (!xn) return;
   ss = block_sum_256(ss, red);
   float rs = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<T>(xr[i] * rs * to_float(g[i]));
+  for (int i = threadIdx.x; i < d; i += 256) xn[(int64_t)r * d + i] = from_float<TO>(xr[i] * rs * to_float(g[i]));
 }
 
 // Fast path for d == 4 * blockDim (d = 4096 with 1024 threads): every thread owns one float4 of the row, all
 // partial loads are issued at once, and the row never leaves registers between the two halves.
-template <typename T>
+template <typename T, typename TO = T>
 __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __restrict__ x, Partials part,
-                                                                     const T* __restrict__ g, T* __restrict__ xn,
+                                                                     const T* __restrict__ g, TO* __restrict__ xn,
                                                                      int d, float eps, int rows, RopeJob rope) {
   if ((int)blockIdx.x >= rows) {
     rope_table_entry((blockIdx.x - rows) * 1024 + threadIdx.x, rope.tree, rope.seq_len, rope.B, rope.max_prefix, rope.half,
@@ -155,19 +155,31 @@ __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __re
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float rs = 1.0f / sqrtf(tot / (float)d + eps);
   const Quad<T> gi = *reinterpret_cast<const Quad<T>*>(g + i);  // gains and output: one 8- or 16-byte access each
-  Quad<T> o;
-  o.v[0] = from_float<T>(v.x * rs * to_float(gi.v[0]));
-  o.v[1] = from_float<T>(v.y * rs * to_float(gi.v[1]));
-  o.v[2] = from_float<T>(v.z * rs * to_float(gi.v[2]));
-  o.v[3] = from_float<T>(v.w * rs * to_float(gi.v[3]));
-  *reinterpret_cast<Quad<T>*>(xn + (int64_t)r * d + i) = o;
+  Quad<TO> o;
+  o.v[0] = from_float<TO>(v.x * rs * to_float(gi.v[0]));
+  o.v[1] = from_float<TO>(v.y * rs * to_float(gi.v[1]));
+  o.v[2] = from_float<TO>(v.z * rs * to_float(gi.v[2]));
+  o.v[3] = from_float<TO>(v.w * rs * to_float(gi.v[3]));
+  *reinterpret_cast<Quad<TO>*>(xn + (int64_t)r * d + i) = o;
 }
 
-static int launch_norm_with_rope(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
-                                 float eps, RopeJob rope, hipStream_t st) {
+// out_dtype: element type of xn.  It differs from dtype (the gains' type) in one case only: a bf16 model whose
+// feed-forward block takes binary16 operands.
+static int launch_norm_with_rope(int dtype, int out_dtype, float* x, const Partials& part, const void* g, void* xn,
+                                 int rows, int d, float eps, RopeJob rope, hipStream_t st) {
   ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
   const int entries = rope.n_blocks ? rope.B * host_tree(rope.tree)->T * rope.half : 0;
+  if (out_dtype != dtype) {
+    MDZ_REQUIRE(dtype == MDZ_BF16 && out_dtype == MDZ_FP16 && rope.n_blocks == 0, MDZ_EINVAL,
+                "norm: only bf16 gains with binary16 output may differ in type");
+    if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0)
+      residual_rmsnorm_vec4_kernel<bf16_t, f16_t><<<rows, 1024, 0, st>>>(x, part, (const bf16_t*)g, (f16_t*)xn, d, eps, rows, rope);
+    else
+      residual_rmsnorm_kernel<bf16_t, f16_t><<<rows, 256, 0, st>>>(x, part, (const bf16_t*)g, (f16_t*)xn, d, eps, rows, rope);
+    MDZ_LAUNCH_CHECK();
+    return MDZ_OK;
+  }
   if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0) {
     rope.n_blocks = (entries + 1023) / 1024;
     MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows + rope.n_blocks, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d,
@@ -182,15 +194,15 @@ static int launch_norm_with_rope(int dtype, float* x, const Partials& part, cons
 }
 
 int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
-                            float eps, hipStream_t st) {
-  return launch_norm_with_rope(dtype, x, part, g, xn, rows, d, eps, RopeJob{}, st);
+                            float eps, hipStream_t st, int out_dtype) {
+  return launch_norm_with_rope(dtype, out_dtype < 0 ? dtype : out_dtype, x, part, g, xn, rows, d, eps, RopeJob{}, st);
 }
 
 int launch_first_norm_and_rope_table(int dtype, float* x, const void* g, void* xn, int rows, int d, float eps, int tree,
                                      const int32_t* seq_len, int B, int max_prefix, int head_dim, float rope_base, float* cs,
                                      int32_t* status, hipStream_t st) {
   RopeJob rope{seq_len, cs, status, tree, B, max_prefix, head_dim / 2, 1, log2((double)rope_base)};
-  return launch_norm_with_rope(dtype, x, single_slot(nullptr, 0, 0), g, xn, rows, d, eps, rope, st);
+  return launch_norm_with_rope(dtype, dtype, x, single_slot(nullptr, 0, 0), g, xn, rows, d, eps, rope, st);
 }
 
 // grid (B*T, query heads), block = head_dim/2 threads... generalised: threads stride over i < half.  The QKV GEMM

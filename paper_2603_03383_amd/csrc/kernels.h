@@ -33,8 +33,9 @@ struct Partials {
 inline Partials single_slot(const float* p, int64_t stride, int64_t ld) { return Partials{p, p ? 1 : 0, stride, ld, 1, 1, 0, 0}; }
 
 // ---- layout movers (layout.hip) ------------------------------------------------------------------
+// to_f16: the source is bf16 and the packed copy holds the same values as binary16
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
-                       int64_t tile_offset, int64_t tile_stride, hipStream_t st);
+                       int64_t tile_offset, int64_t tile_stride, hipStream_t st, bool to_f16 = false);
 int launch_kv_copy(int dtype, const KvGeom& g, void* kc, void* vc, int layer, int seq, int pos0, int n,
                    void* k_rows, void* v_rows, bool to_cache, hipStream_t st);
 // status (nullable): device word that receives MDZ_STATUS_SEQ_RANGE when a length arrives out of range
@@ -48,9 +49,9 @@ int launch_fill_zero(void* p, int64_t bytes, hipStream_t st);
 int launch_embed(int dtype, const void* embed, const int32_t* tokens, float* x, int rows, int d, int vocab,
                  hipStream_t st);
 // x[r] += sum of partials (skipped if part.p == NULL); then xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g rounded
-// to the storage dtype (skipped if xn == NULL)
+// to the storage dtype (skipped if xn == NULL); out_dtype >= 0 names another type for xn (binary16 beside bf16 gains)
 int launch_residual_rmsnorm(int dtype, float* x, const Partials& part, const void* g, void* xn, int rows, int d,
-                            float eps, hipStream_t st);
+                            float eps, hipStream_t st, int out_dtype = -1);
 // the first norm of a verify pass (no residual update: xn = RMSNorm(x; g)) and the pass's RoPE table in ONE launch:
 // cos/sin of (S_b + depth[n]) * base^(-2i/hd), evaluated in double: cs [B*T][hd/2][2] fp32; status (nullable)
 // receives MDZ_STATUS_SEQ_RANGE when a length arrives out of range

@@ -5,8 +5,8 @@
 
 namespace mdz {
 
-template <typename T>
-__global__ void pack_weight_kernel(const T* __restrict__ src, int64_t n_rows, int64_t k, T* __restrict__ dst,
+template <typename T, typename TD = T>
+__global__ void pack_weight_kernel(const T* __restrict__ src, int64_t n_rows, int64_t k, TD* __restrict__ dst,
                                    int64_t kp, int64_t tile_offset, int64_t tile_stride, int64_t n_rows_pad) {
   constexpr int R = Packed<T>::kTileRows;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -14,12 +14,16 @@ __global__ void pack_weight_kernel(const T* __restrict__ src, int64_t n_rows, in
   int64_t n = idx / kp, kk = idx % kp;
   int64_t dst_row = (tile_offset + (n / R) * tile_stride) * R + n % R;
   T v = (n < n_rows && kk < k) ? src[n * k + kk] : from_float<T>(0.f);
-  dst[Packed<T>::index(dst_row, kk, kp)] = v;
+  if constexpr (std::is_same<T, TD>::value)
+    dst[Packed<T>::index(dst_row, kk, kp)] = v;
+  else  // every bf16 value inside binary16's normal range is a binary16 value: the copy is exact there
+    dst[Packed<T>::index(dst_row, kk, kp)] = from_float<TD>(to_float(v));
 }
 
 int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
-                       int64_t tile_offset, int64_t tile_stride, hipStream_t st) {
+                       int64_t tile_offset, int64_t tile_stride, hipStream_t st, bool to_f16) {
   ProfScope prof_(PROF_MISC, st);
+  MDZ_REQUIRE(!to_f16 || dtype == MDZ_BF16, MDZ_EINVAL, "pack: only a bf16 matrix is repacked as binary16");
   const int R = is_16bit(dtype) ? kTileRowsBf16 : kTileRowsF32;
   const int64_t kp = is_16bit(dtype) ? Packed<bf16_t>::padded_k(k) : k;
   const int64_t n_pad = round_up(n_rows, R);
@@ -35,7 +39,10 @@ int launch_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
   const int64_t total = n_pad * kp;
   const int threads = 256;
   const int64_t blocks = (total + threads - 1) / threads;
-  if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
+  if (to_f16)
+    pack_weight_kernel<bf16_t, f16_t><<<dim3((unsigned)blocks), threads, 0, st>>>(
+        (const bf16_t*)src, n_rows, k, (f16_t*)dst, kp, tile_offset, tile_stride, n_pad);
+  else if (is_16bit(dtype))  // bf16 and fp16 move as the same 16-bit words
     pack_weight_kernel<bf16_t><<<dim3((unsigned)blocks), threads, 0, st>>>(
         (const bf16_t*)src, n_rows, k, (bf16_t*)dst, kp, tile_offset, tile_stride, n_pad);
   else

@@ -137,6 +137,8 @@ int launch_rope_attention(int dtype, int tree, const Partials& qkv, const float*
 // key/value heads of a model (0 in the descriptor: as many as query heads) and the width of its K (or V) projection
 static int kv_heads(const mdz_model_desc& m) { return m.n_kv_heads > 0 ? m.n_kv_heads : m.n_heads; }
 static int kv_width(const mdz_model_desc& m) { return kv_heads(m) * m.head_dim; }
+// operand type of the feed-forward block's two products
+static int ffn_dtype(const mdz_model_desc& m) { return m.ffn_f16 ? (int)MDZ_FP16 : m.dtype; }
 
 struct Workspace {
   int64_t rope_cs, x, xn, part, q, att, u, logits, h, z, hlogits, sel, sel_bytes, attn_scratch, total;
@@ -211,6 +213,8 @@ static int check_model(const mdz_model_desc* m) {
   MDZ_REQUIRE(!is_16bit(m->dtype) || (m->d % kKStepBf16 == 0 && m->ffn % kKStepBf16 == 0), MDZ_ESHAPE,
               "bf16 / fp16: d and ffn must be multiples of %d", kKStepBf16);
   MDZ_REQUIRE(m->rms_eps >= 0.f && m->rope_base > 1.f, MDZ_EINVAL, "bad rms_eps / rope_base");
+  MDZ_REQUIRE(m->ffn_f16 == 0 || (m->ffn_f16 == 1 && m->dtype == MDZ_BF16), MDZ_EINVAL,
+              "ffn_f16 is 0 or 1 and applies to bf16 models only (ffn_f16 %d, dtype %d)", m->ffn_f16, m->dtype);
   return MDZ_OK;
 }
 
@@ -267,22 +271,25 @@ static int run_layer(const mdz_model_desc& m, const mdz_layer_weights& lw, int l
   void* u = ws + w.u;
   Partials pr;
   const int qkv_cols = m.d + 2 * kv_width(m);
+  // operand type of the feed-forward block: binary16 for a bf16 model that asks for it (wgateup and wdown are then
+  // packed as binary16 and the block's two activations are rounded to binary16), else the storage type
+  const int fdt = ffn_dtype(m);
   if ((rc = launch_gemm(m.dtype, xn, lw.wqkv, part, rows, qkv_cols, m.d, qkv_cols, ms, &pr, st))) return rc;
   if ((rc = launch_rope_attention(m.dtype, m.tree, pr, cs, q, g, kv->k, kv->v, layer, seq_len, B, max_prefix, att,
                                   ws + w.attn_scratch, w.total - w.attn_scratch, st)))
     return rc;
   if ((rc = launch_gemm(m.dtype, att, lw.wo, part, rows, m.d, m.d, m.d, ms, &pr, st))) return rc;
-  if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st))) return rc;
+  if ((rc = launch_residual_rmsnorm(m.dtype, x, pr, lw.g_ffn, xn, rows, m.d, m.rms_eps, st, fdt))) return rc;
   // SwiGLU in the GEMM's epilogue where a workgroup ends up with whole gate/up column pairs
-  if (gemm_large_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {
-    if ((rc = launch_gemm_large_swiglu(m.dtype, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
-  } else if (rows <= 64 && gemm_mfma_swiglu_supported(m.dtype, rows, 2 * m.ffn, m.d)) {
-    if ((rc = launch_gemm_mfma_swiglu(m.dtype, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
+  if (gemm_large_swiglu_supported(fdt, rows, 2 * m.ffn, m.d)) {
+    if ((rc = launch_gemm_large_swiglu(fdt, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
+  } else if (rows <= 64 && gemm_mfma_swiglu_supported(fdt, rows, 2 * m.ffn, m.d)) {
+    if ((rc = launch_gemm_mfma_swiglu(fdt, xn, lw.wgateup, u, rows, 2 * m.ffn, m.d, st))) return rc;
   } else {
-    if ((rc = launch_gemm(m.dtype, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
-    if ((rc = launch_swiglu(m.dtype, pr, u, rows, m.ffn, st))) return rc;
+    if ((rc = launch_gemm(fdt, xn, lw.wgateup, part, rows, 2 * m.ffn, m.d, 2 * m.ffn, ms, &pr, st))) return rc;
+    if ((rc = launch_swiglu(fdt, pr, u, rows, m.ffn, st))) return rc;
   }
-  if ((rc = launch_gemm(m.dtype, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, &pr, st))) return rc;
+  if ((rc = launch_gemm(fdt, u, lw.wdown, part, rows, m.d, m.ffn, m.d, ms, &pr, st))) return rc;
   return launch_residual_rmsnorm(m.dtype, x, pr, g_next, xn_next, rows, m.d, m.rms_eps, st);
 }
 
@@ -395,6 +402,14 @@ int medusa_pack_weight(int dtype, const void* src, int64_t n_rows, int64_t k, vo
   MDZ_REQUIRE(src && dst, MDZ_EINVAL, "pack: NULL pointer");
   MDZ_REQUIRE(n_rows > 0 && k > 0 && dst_rows >= n_rows, MDZ_EINVAL, "pack: bad sizes");
   return launch_pack_weight(dtype, src, n_rows, k, dst, dst_rows, tile_offset, tile_stride, (hipStream_t)stream);
+}
+
+int medusa_pack_weight_bf16_as_f16(const void* src, int64_t n_rows, int64_t k, void* dst, int64_t dst_rows,
+                                   int64_t tile_offset, int64_t tile_stride, void* stream) {
+  MDZ_REQUIRE(src && dst, MDZ_EINVAL, "pack: NULL pointer");
+  MDZ_REQUIRE(n_rows > 0 && k > 0 && dst_rows >= n_rows, MDZ_EINVAL, "pack: bad sizes");
+  return launch_pack_weight(MDZ_BF16, src, n_rows, k, dst, dst_rows, tile_offset, tile_stride, (hipStream_t)stream,
+                            true);
 }
 
 int64_t medusa_kv_bytes(const mdz_kv_desc* kv) {

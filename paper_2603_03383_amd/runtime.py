@@ -21,9 +21,10 @@ class DeviceModel:
     """Packed weights of one decoder (+ Medusa heads) on one GPU."""
 
     def __init__(self, *, d, n_heads, head_dim, ffn, vocab, n_layers, dtype: str, tree: str, n_kv_heads: int = 0, rms_eps=1e-5,
-                 rope_base=10000.0, device="cuda:0"):
+                 rope_base=10000.0, device="cuda:0", ffn_f16: bool = False):
         self.desc = B.ModelDesc(d, n_heads, head_dim, ffn, vocab, n_layers, B.DTYPES[dtype], B.TREES[tree], rms_eps,
-                                rope_base, n_kv_heads)
+                                rope_base, n_kv_heads, int(ffn_f16))
+        self.ffn_f16 = bool(ffn_f16)
         self.kv_heads = n_kv_heads or n_heads
         self.device = torch.device(device)
         self.dtype = B.DTYPES[dtype]
@@ -49,8 +50,10 @@ class DeviceModel:
     def _dev(self, t: torch.Tensor) -> torch.Tensor:
         return t.to(self.device, self.tdtype).contiguous()
 
-    def pack(self, mats: Sequence[torch.Tensor], interleave: bool = False) -> torch.Tensor:
-        """Stacks (or tile-interleaves) row-major [n_i, k] matrices into one packed matrix."""
+    def pack(self, mats: Sequence[torch.Tensor], interleave: bool = False, as_f16: bool = False) -> torch.Tensor:
+        """Stacks (or tile-interleaves) row-major [n_i, k] matrices into one packed matrix.  as_f16: a bf16 model's
+        feed-forward matrices, stored as binary16."""
+        pack_one = (lambda _dt, *a: B.medusa_pack_weight_bf16_as_f16(*a)) if as_f16 else B.medusa_pack_weight
         k = mats[0].shape[1]
         total = sum(m.shape[0] for m in mats)
         dst = self._alloc_packed(total, k)
@@ -58,9 +61,9 @@ class DeviceModel:
         for i, m in enumerate(mats):
             m = self._dev(m)
             if interleave:
-                B.medusa_pack_weight(self.dtype, m, dst, total, i, len(mats))
+                pack_one(self.dtype, m, dst, total, i, len(mats))
             else:
-                B.medusa_pack_weight(self.dtype, m, dst, total, off // self.R, 1)
+                pack_one(self.dtype, m, dst, total, off // self.R, 1)
                 off += m.shape[0]
         torch.cuda.synchronize(self.device)          # the row-major sources may be freed by the caller now
         return dst
@@ -73,7 +76,8 @@ class DeviceModel:
     # -- model assembly --------------------------------------------------------------------------
     def add_layer(self, wq, wk, wv, wo, wgate, wup, wdown, g_attn, g_ffn) -> None:
         lw = B.LayerWeights(self.pack([wq, wk, wv]).data_ptr(), self.pack([wo]).data_ptr(),
-                            self.pack([wgate, wup], interleave=True).data_ptr(), self.pack([wdown]).data_ptr(),
+                            self.pack([wgate, wup], interleave=True, as_f16=self.ffn_f16).data_ptr(),
+                            self.pack([wdown], as_f16=self.ffn_f16).data_ptr(),
                             self._gain(g_attn).data_ptr(), self._gain(g_ffn).data_ptr())
         self._layers.append(lw)
 
@@ -129,7 +133,7 @@ class DeviceModel:
         other = copy.copy(self)
         d = self.desc
         other.desc = B.ModelDesc(d.d, d.n_heads, d.head_dim, d.ffn, d.vocab, d.n_layers, d.dtype, B.TREES[tree],
-                                 d.rms_eps, d.rope_base, d.n_kv_heads)
+                                 d.rms_eps, d.rope_base, d.n_kv_heads, d.ffn_f16)
         other.tree = B.TREES[tree]
         other.tree_info = B.medusa_tree_info(other.tree)
         keep = len(self._heads) if other.tree_info["K"] == len(self._heads) else 0

@@ -60,6 +60,14 @@ def test_argument_errors_are_status_codes():
         with pytest.raises(P.MedusaError) as e:
             P.medusa_workspace_bytes(mm, 1, 64)
         assert e.value.status in (-1, -2)
+    # binary16 feed-forward operands are an option of bf16 models only
+    ok = P.ModelDesc(256, 4, 64, 704, 1024, 2, P.MDZ_BF16, P.MDZ_TREE_15, 1e-5, 1e4, 0, 1)
+    assert P.medusa_workspace_bytes(ok, 1, 64) > 0
+    for dtype, flag in [(P.MDZ_FP32, 1), (P.MDZ_FP16, 1), (P.MDZ_BF16, 2)]:
+        bad = P.ModelDesc(256, 4, 64, 704, 1024, 2, dtype, P.MDZ_TREE_15, 1e-5, 1e4, 0, flag)
+        with pytest.raises(P.MedusaError) as e:
+            P.medusa_workspace_bytes(bad, 1, 64)
+        assert e.value.status == -1 and "ffn_f16" in str(e.value)
     with pytest.raises(P.MedusaError):
         P.medusa_tree_info(5)
     with pytest.raises(P.MedusaError):

@@ -477,6 +477,16 @@ def _oracle_steps_streamed(w, tokens_by_seq, tree, kv_rows=None):
     return out
 
 
+_FULL_DEPTH_REF = {}
+
+
+def full_depth_reference(w, tokens, S, tree):
+    """The oracle's 32-layer pass of one seed, computed once per test session (about a minute of CPU work)."""
+    if w.seed not in _FULL_DEPTH_REF:
+        _FULL_DEPTH_REF[w.seed] = _oracle_step_streamed(w, tokens, S, tree, kv_rows={0, 31})
+    return _FULL_DEPTH_REF[w.seed]
+
+
 @pytest.mark.parametrize("seed", [W.BASE_SEED, W.BASE_SEED + 1], ids=["base_seed", "second_seed"])
 def test_cfg3_full_depth_32_layers_every_logit(seed):
     """The metric's own workload: 32 layers, prefix 1024, all 64 x 128000 logits against the oracle, on two seeds."""
@@ -486,7 +496,7 @@ def test_cfg3_full_depth_32_layers_every_logit(seed):
     tree = U.oracle_tree(w)
     T = tree["T"]
     tokens = W.random_tokens(w, "full_depth_tree", (T,)).numpy()
-    ref = _oracle_step_streamed(w, tokens, S, tree, kv_rows={0, 31})
+    ref = full_depth_reference(w, tokens, S, tree)
     dm = G.device_model(w, heads=False)
     kv = G.device_kv_random_prefix(dm, w, cap=S + T)
     buf = P.StepBuffers(dm, 1, S, want_logits=True)
@@ -529,6 +539,35 @@ def test_cfg3_full_depth_32_layers_every_logit(seed):
     torch.cuda.synchronize()
     lg3 = buf2.logits[0].cpu().numpy()
     assert np.abs(lg3 - lg[perm]).max() <= 2e-3 * scale
+
+
+def test_cfg3_full_depth_with_binary16_feed_forward_operands():
+    """The same 32-layer pass with the feed-forward products on binary16 operands (a bf16 model's option): same
+    oracle, same bound, and the error has to come out well under the plain bf16 path's (its two largest rounding terms
+    shrink eightfold)."""
+    w = W.CONFIGS["cfg3_step_1k"].with_(ffn_f16=True)
+    S = w.prefix[0]
+    tree = U.oracle_tree(w)
+    T = tree["T"]
+    tokens = W.random_tokens(w, "full_depth_tree", (T,)).numpy()
+    ref = full_depth_reference(w, tokens, S, tree)
+    dm = G.device_model(w, heads=False)
+    kv = G.device_kv_random_prefix(dm, w, cap=S + T)
+    buf = P.StepBuffers(dm, 1, S, want_logits=True)
+    buf.tree_tokens.copy_(_i32(tokens).view(1, T))
+    seq_len = _i32([S])
+    P.run_step(dm, kv, buf, None, None, None, seq_len, with_heads=False)
+    torch.cuda.synchronize()
+    lg = buf.logits[0].cpu().numpy()
+    scale = _scale(ref["logits"])
+    err = np.abs(lg - ref["logits"]).max()
+    print(f"cfg3 full depth, binary16 feed-forward operands: logits err/scale {err / scale:.3e}")
+    assert err <= 8e-3 * scale
+    assert np.abs(U.to_np(buf.hidden[0]) - ref["hidden"]).max() <= 8e-3 * _scale(ref["hidden"])
+    gpu_am = buf.node_argmax[0].cpu().numpy()
+    check_argmax_near_tie(gpu_am, lg, ref["logits"], 8e-3 * scale)
+    acc = O.accept_longest_prefix(tree, tokens, gpu_am)
+    assert int(buf.accept_len[0]) == acc["accept_len"] and int(seq_len[0]) == S + acc["accept_len"]
 
 
 @pytest.mark.parametrize("S", [4096, 8192, 16384])

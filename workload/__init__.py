@@ -166,6 +166,7 @@ class Workload:
     kv_quant: str = ""         # "" | "fp8e4m3": cache rows stored as 8-bit codes with one fp32 scale per row
     gain_std: float = 0.3      # RMSNorm gains are 1 + gain_std * z (0: all ones)
     head_bias_std: float = 0.0  # Medusa-head bias b1 ~ head_bias_std * z (0: the heads have no bias)
+    ffn_f16: bool = False      # device-side option of a bf16 model (binary16 feed-forward operands); changes no input
 
     @property
     def kv_heads(self) -> int:
