@@ -231,7 +231,9 @@ int tree_verify_layer_static(const mdz_model_desc* model, const mdz_layer_weight
 /* Section 3.2, the whole pass: embedding gather of tree_tokens [B, T] -> every layer as above -> final
  * RMSNorm -> LM head -> per-node argmax (ties -> lowest id).  Outputs: node_argmax [B, T];
  * hidden_out (nullable) [B, T, d] storage dtype = the post-final-norm hidden (what medusa_heads reads);
- * logits_opt (nullable) [B, T, vocab] fp32. */
+ * logits_opt (nullable) [B, T, vocab] fp32.  With logits_opt NULL the logits are not materialised where the shape
+ * allows it (16-bit storage, B * T <= 64): the LM-head kernel keeps each row's best column itself; node_argmax is the
+ * same either way, bit for bit (the selection order is total: value descending, then lowest id). */
 int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const int32_t* tree_tokens,
                      const mdz_kv_desc* kv, const int32_t* seq_len, int B, int max_prefix, int32_t* node_argmax,
                      void* hidden_out, float* logits_opt, void* ws, int64_t ws_bytes, void* stream);

@@ -20,6 +20,10 @@
 //     workgroup): waves 0/2 hold the gate columns and waves 1/3 the up columns of the same 32 features; at the end of
 //     a band the up sums cross to their partner through LDS and SiLU(gate) * up is written as E, so neither the
 //     fp32 sums nor a second kernel are needed.
+//   * ARGMAX (the LM head of a verify pass, whole bands per workgroup, when the caller wants no logits): at the end
+//     of a band a wave turns its 64 x 32 sums through LDS so that lane m holds row m, scans the 32 columns and keeps
+//     the row's best (value, column) so far in two registers; at the end of its range it writes one candidate per
+//     row.  A small kernel merges the workgroups' candidates; the fp32 logits never exist in memory.
 #include "kernels.h"
 
 namespace mdz {
@@ -29,12 +33,13 @@ typedef u32x4_t u32x4;
 
 __device__ inline float silu_mfma(float v) { return v / (1.0f + expf(-v)); }
 
-template <int WPB, int NT, int MT, int CK, typename E, bool SWIGLU = false>
+template <int WPB, int NT, int MT, int CK, typename E, bool SWIGLU = false, bool ARGMAX = false>
 __global__ void __launch_bounds__(WPB * 64)
     gemm_mfma_kernel(const E* __restrict__ X, int M, int K, const E* __restrict__ Wp, int n_tiles,
                      int n_stages, float* __restrict__ P, int64_t ldp, int64_t part_stride, int whole_bands,
-                     E* __restrict__ Uout = nullptr) {
+                     E* __restrict__ Uout = nullptr, ArgCand* __restrict__ cand = nullptr) {
   static_assert(!SWIGLU || (WPB == 4 && NT == 1), "the SwiGLU epilogue pairs waves 0/1 and 2/3");
+  static_assert(!ARGMAX || (NT == 1 && !SWIGLU), "the argmax epilogue scans one tile per wave");
   constexpr int ROWS = MT * 32;
   constexpr int KH = CK / 32;                       // MFMA k-steps per half stage
   constexpr int LROW = CK * 2 + 16;                 // bytes per staged X row (16 B pad)
@@ -54,7 +59,19 @@ __global__ void __launch_bounds__(WPB * 64)
     u_lo = (int)(w * U / G);
     u_hi = (int)((w + 1) * U / G);
   }
-  if (u_lo >= u_hi) return;
+  // ARGMAX: the best (value, column) of row (lane % ROWS) over the tiles this wave has finished; written as
+  // candidate [row][workgroup * WPB + wave] when the range ends (also by a workgroup with an empty range)
+  float best_v = -INFINITY;
+  int best_i = kNoIndex;
+  auto write_cand = [&]() {
+    if constexpr (ARGMAX) {
+      if (lane < ROWS && lane < M) cand[(int64_t)lane * (G * WPB) + w * WPB + wave] = ArgCand{best_v, best_i};
+    }
+  };
+  if (u_lo >= u_hi) {
+    write_cand();
+    return;
+  }
   const int nst256 = (K + kStageFeatures - 1) / kStageFeatures;  // stages of the packed layout
 
   f32x16 acc[NT][MT];
@@ -168,6 +185,31 @@ __global__ void __launch_bounds__(WPB * 64)
       zero_acc();
       return;
     }
+    if constexpr (ARGMAX) {
+      // the wave's own turn buffer behind the two X stages: [row][33] floats (no other wave touches it: no barrier)
+      float* turn = reinterpret_cast<float*>(lds_raw + 2 * ROWS * LROW) + wave * ROWS * 33;
+      const int col = lane & 31, rbase = (lane >> 5) * 4;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) turn[(mt * 32 + 8 * (r >> 2) + rbase + (r & 3)) * 33 + col] = acc[0][mt][r];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const int tile = b * WPB + wave;
+      if (tile < n_tiles) {
+        const float* rp = turn + (lane % ROWS) * 33;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+          const float v = rp[c];
+          if (precedes(v, tile * 32 + c, best_v, best_i)) best_v = v, best_i = tile * 32 + c;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      zero_acc();
+      return;
+    }
     // slot = this workgroup's rank among the ranges that touch the band (see Partials::count)
     const int slot = whole_bands ? 0 : (int)(w - Partials::owner((uint32_t)b * n_stages, U, G));
     float* out = P + (int64_t)slot * part_stride;
@@ -248,6 +290,7 @@ __global__ void __launch_bounds__(WPB * 64)
     store_x(0);
     __syncthreads();
   }
+  write_cand();
 }
 
 struct GemmPlan {
@@ -403,6 +446,33 @@ static int launch_gemm_mfma_swiglu_t(const void* X, const void* Wp, void* U, int
 #undef MDZ_SWIGLU_CASE
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
+}
+
+// The LM head of a verify pass when only the per-row argmax is wanted: no logits are written.  cand receives
+// M x gemm_mfma_argmax_cands(...) candidates (one per workgroup and wave); launch_argmax_merge picks each row's best.
+bool gemm_mfma_argmax_supported(int dtype, int M, int N, int K) {
+  return gemm_mfma_supported(dtype, M, N, K) && N / 128 >= num_cus() / 2;  // enough bands to fill the chip unsplit
+}
+int gemm_mfma_argmax_cands(int M, int N, int K) { return plan_gemm(M, N, K, 1).grid * 4; }
+
+template <typename E>
+static int launch_gemm_mfma_argmax_t(const void* X, const void* Wp, int M, int N, int K, ArgCand* cand, hipStream_t st) {
+  const GemmPlan p = plan_gemm(M, N, K, 1);
+  ProfScope prof_(p.mt == 2 ? PROF_GEMM_W64 : PROF_GEMM_W32, st);
+  const int n_tiles = N / 32, n_stages = K / 128, bands = (n_tiles + 3) / 4;
+  MDZ_REQUIRE(p.wpb == 4 && p.nt == 1 && p.ck == 128 && p.whole, MDZ_EUNSUPPORTED, "gemm: no argmax kernel for plan %d,%d,%d",
+              p.wpb, p.nt, p.ck);
+  MDZ_REQUIRE((int64_t)bands * n_stages * p.grid < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: %d x %d units overflow", bands,
+              n_stages);
+#define MDZ_ARGMAX_CASE(MT)                                                                                            {                                                                                                                       constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 4 * MT * 32 * 33 * 4;                                        MDZ_SET_LDS_ONCE((gemm_mfma_kernel<4, 1, MT, 128, E, false, true>), lds_bytes);                                       gemm_mfma_kernel<4, 1, MT, 128, E, false, true><<<p.grid, 256, lds_bytes, st>>>(                                          (const E*)X, M, K, (const E*)Wp, n_tiles, n_stages, nullptr, 0, 0, 1, nullptr, cand);                           }
+  if (p.mt == 1) MDZ_ARGMAX_CASE(1) else MDZ_ARGMAX_CASE(2)
+#undef MDZ_ARGMAX_CASE
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
+
+int launch_gemm_mfma_argmax(int dtype, const void* X, const void* Wp, int M, int N, int K, ArgCand* cand, hipStream_t st) {
+  MDZ_WITH_ELEM16(dtype, return launch_gemm_mfma_argmax_t<E>(X, Wp, M, N, K, cand, st));
 }
 
 int launch_gemm_mfma_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {

@@ -81,6 +81,16 @@ int launch_head_residual(int dtype, const void* h, const Partials& pre, int64_t 
 int launch_store_rows(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
 
 // ---- selection kernels (select.hip) -----------------------------------------------------------------
+// a (value, column) candidate of a row; index kNoIndex marks an empty one
+struct ArgCand {
+  float v;
+  int i;
+};
+constexpr int kNoIndex = 0x7FFFFFFF;
+// a precedes b in the selection order: value descending, then index ascending (total on non-NaN values)
+__device__ inline bool precedes(float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); }
+// out[r] = index of the best of cand[r][0..n_cand) in that order (-1 if all are empty)
+int launch_argmax_merge(const ArgCand* cand, int rows, int n_cand, int32_t* out, hipStream_t st);
 // out[r] = argmax_v logits[r][v], ties -> lowest v
 // (scratch: topk_scratch_bytes(rows) bytes enable the two-stage kernels for long rows; may be NULL)
 int launch_argmax(const float* logits, int rows, int V, int64_t ld, int32_t* out, void* scratch, int64_t scratch_bytes,

@@ -53,6 +53,9 @@ int launch_gemm_large(int dtype, const void* X, const void* Wp, float* P, int M,
 
 bool gemm_mfma_swiglu_supported(int dtype, int M, int N, int K);
 int launch_gemm_mfma_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st);
+bool gemm_mfma_argmax_supported(int dtype, int M, int N, int K);
+int gemm_mfma_argmax_cands(int M, int N, int K);
+int launch_gemm_mfma_argmax(int dtype, const void* X, const void* Wp, int M, int N, int K, ArgCand* cand, hipStream_t st);
 bool gemm_large_swiglu_supported(int dtype, int M, int N, int K);
 int launch_gemm_large_swiglu(int dtype, const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st);
 
@@ -633,6 +636,16 @@ int tree_verify_step(const mdz_model_desc* model, const mdz_weights* w, const in
     if ((rc = run_layer(m, w->layers[l], l, x, kv, seq_len, B, max_prefix, wsb, L,
                         last ? w->g_final : w->layers[l + 1].g_attn, last ? hid : xn, st)))
       return rc;
+  }
+  // No logits asked for: the LM head keeps each row's best column in its epilogue and a small merge finishes the
+  // argmax, so the [rows, vocab] fp32 logits are neither written nor read back.
+  if (!logits_opt && gemm_mfma_argmax_supported(m.dtype, rows, m.vocab, m.d)) {
+    const int n_cand = gemm_mfma_argmax_cands(rows, m.vocab, m.d);
+    if ((int64_t)rows * n_cand * (int64_t)sizeof(ArgCand) <= L.sel_bytes) {
+      ArgCand* cand = (ArgCand*)(wsb + L.sel);
+      if ((rc = launch_gemm_mfma_argmax(m.dtype, hid, w->lm_head, rows, m.vocab, m.d, cand, st))) return rc;
+      return launch_argmax_merge(cand, rows, n_cand, node_argmax, st);
+    }
   }
   float* logits = logits_opt ? logits_opt : (float*)(wsb + L.logits);
   Partials pr;

@@ -7,12 +7,7 @@
 
 namespace mdz {
 
-struct Best {
-  float v;
-  int i;
-};
-// a precedes b in (value descending, index ascending) order
-__device__ inline bool precedes(float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); }
+typedef ArgCand Best;
 
 // Best of the wave's 64 candidates, in every lane.  Within a row of 16 lanes the exchange runs on data-parallel
 // primitives (lane ^ 1, lane ^ 2 by quad permutation, then the mirrored lane of the half row and of the row: four
@@ -53,7 +48,28 @@ __device__ inline Best block_best_256(Best a, Best* smem4) {
   return r;
 }
 
-constexpr int kNoIndex = 0x7FFFFFFF;
+// One workgroup per row: the best of the row's candidates (pairs left by the LM-head GEMM's argmax epilogue, one per
+// workgroup and wave; index kNoIndex = empty).
+__global__ void __launch_bounds__(256) argmax_merge_kernel(const ArgCand* __restrict__ cand, int n_cand,
+                                                           int32_t* __restrict__ out) {
+  __shared__ Best smem4[4];
+  const int row = blockIdx.x;
+  Best b{-INFINITY, kNoIndex};
+  for (int c = threadIdx.x; c < n_cand; c += 256) {
+    const Best h = cand[(int64_t)row * n_cand + c];
+    if (h.i != kNoIndex && precedes(h.v, h.i, b.v, b.i)) b = h;
+  }
+  b = block_best_256(b, smem4);
+  if (threadIdx.x == 0) out[row] = b.i == kNoIndex ? -1 : b.i;
+}
+
+int launch_argmax_merge(const ArgCand* cand, int rows, int n_cand, int32_t* out, hipStream_t st) {
+  ProfScope prof_(PROF_SELECT, st);
+  if (rows == 0) return MDZ_OK;
+  argmax_merge_kernel<<<rows, 256, 0, st>>>(cand, n_cand, out);
+  MDZ_LAUNCH_CHECK();
+  return MDZ_OK;
+}
 
 // One block per row. Pass p selects the best element that strictly follows the previous pick.
 __global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ logits, int V, int64_t ld, int k,
