@@ -4,8 +4,8 @@
 One "step" = one pass of the whole hot path over one batch of seeded synthetic input, all four C-ABI
 calls: medusa_heads -> tree_verify_step -> accept_longest_prefix -> kv_compact, inputs resident in HBM.
 Prints ONE JSON line: steps/s (value), ms/step, achieved HBM GB/s of the whole step, a `roofline`
-object for the dominant kernel family (the weight-streaming GEMMs, timed with HIP events on the launch
-stream in instrumented steps that follow the timed region) and a `cpu_baseline` object (the float64
+object for the dominant kernel family (the weight-streaming GEMMs, each launch timed by its own dispatch's start and
+end timestamps in HIP events on the launch stream, in instrumented steps that follow the timed region) and a `cpu_baseline` object (the float64
 oracle timed on this machine's host cores on a bounded sample of the same workload).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_step_1k] [--no-heads]
@@ -117,7 +117,8 @@ def timed(fn, warmup, steps):
 
 
 def profiled(fn, steps, launches_per_step):
-    """{family: {launches, total_us, ...}} over `steps` instrumented runs of fn (HIP events around every launch)."""
+    """{family: {launches, total_us, ...}} over `steps` instrumented runs of fn (HIP events: the GEMM kernels' own start / end
+    timestamps, taken by the dispatch; event records on the stream around every other launch)."""
     import torch
     import paper_2603_03383_amd as P
     P.medusa_profile_begin(steps * launches_per_step)
@@ -355,7 +356,8 @@ def main():
 
     ms = timed(one_step, args.warmup, args.steps)
 
-    # instrumented steps: HIP events around every kernel launch, on the launch stream
+    # instrumented steps: HIP events on the launch stream (a GEMM launch's own start / end timestamps; records around
+    # the other launches)
     prof = profiled(one_step, args.steps, w.n_layers * 12 + 64)
 
     # the autoregressive baseline (Section 4.1): the same weights and prefix, the single-node tree, timed the same way
@@ -462,8 +464,8 @@ def main():
                      "launches_per_step": gemm["launches"] / args.steps,
                      "avg_launch_us": gemm["total_us"] / max(1, gemm["launches"]),
                      "all_gemm_launches_GBps": all_gemm_gbps,
-                     "measured": "HIP events on the launch stream around every launch, %d instrumented steps "
-                                 "after the timed region" % args.steps},
+                     "measured": "HIP events on the launch stream holding each launch's own start and end timestamps "
+                                 "(hipExtLaunchKernelGGL), %d instrumented steps after the timed region" % args.steps},
         "stream_read_ceiling_GBps": {"%.0fMB" % (k / 1e6): v for k, v in ceil.items()},
         "kernel_us_per_step": {k: v["total_us"] / args.steps for k, v in prof.items()},
         "kernel_launches_per_step": {k: v["launches"] / args.steps for k, v in prof.items()},
@@ -483,8 +485,8 @@ def main():
                            "algorithmic_flops_per_launch": flops / (gl["launches"] / args.steps),
                            "launches_per_step": gl["launches"] / args.steps,
                            "avg_launch_us": gl["total_us"] / gl["launches"],
-                           "measured": "HIP events on the launch stream around every launch, %d instrumented steps "
-                                       "after the timed region" % args.steps}
+                           "measured": "HIP events on the launch stream holding each launch's own start and end "
+                                       "timestamps (hipExtLaunchKernelGGL), %d instrumented steps after the timed region" % args.steps}
     if not args.skip_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, with_heads)
     print(json.dumps(out))

@@ -219,7 +219,6 @@ int gemm_large_slots(int M, int N, int K) { return plan_large(M, N, K).ksplit; }
 template <typename E, bool SWIGLU>
 static int launch_gemm_large_t(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp,
                                int64_t part_stride, Partials* res, void* U, hipStream_t st) {
-  ProfScope prof_(PROF_GEMM_LARGE, st);
   const LargePlan p = plan_large(M, N, K);
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
@@ -231,8 +230,9 @@ static int launch_gemm_large_t(const void* X, const void* Wp, float* P, int M, i
   res->n_stages = 1;
   res->split_units = 0;
   const int groups = (p.nb_n + 7) / 8;  // column blocks per XCD
-  gemm_large_kernel<E, SWIGLU><<<dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st>>>(
-      (const E*)X, M, K, (const E*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m, (E*)U);
+  launch_timed(PROF_GEMM_LARGE, gemm_large_kernel<E, SWIGLU>, dim3(8 * groups * p.nb_m, 1, p.ksplit), 256, kLdsBytes, st,
+               (const E*)X, M, K, (const E*)Wp, N / 32, P, (int)ldp, part_stride, p.stages_per_split, p.nb_n, p.nb_m,
+               (E*)U);
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
 }

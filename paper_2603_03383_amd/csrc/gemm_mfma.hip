@@ -389,8 +389,7 @@ template <typename E>
 static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, int N, int K, int64_t ldp, int64_t part_stride,
                               int max_split, Partials* res, hipStream_t st) {
   GemmPlan p = plan_gemm(M, N, K, max_split);
-  ProfScope prof_(p.mt == 2 ? (p.wpb == 4 ? PROF_GEMM_W64 : PROF_GEMM_N64) : (p.wpb == 4 ? PROF_GEMM_W32 : PROF_GEMM_N32),
-                  st);
+  const int tag = p.mt == 2 ? (p.wpb == 4 ? PROF_GEMM_W64 : PROF_GEMM_N64) : (p.wpb == 4 ? PROF_GEMM_W32 : PROF_GEMM_N32);
   const int n_tiles = N / 32, n_stages = K / p.ck;
   MDZ_REQUIRE((int64_t)M * ldp < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: output of %d rows with pitch %lld is too large", M,
               (long long)ldp);
@@ -404,8 +403,8 @@ static int launch_gemm_mfma_t(const void* X, const void* Wp, float* P, int M, in
   if (p.wpb == WPB && p.nt == NT && p.mt == MT && p.ck == CK) {                                              \
     constexpr int lds_bytes = 2 * MT * 32 * (CK * 2 + 16);                                                   \
     MDZ_SET_LDS_ONCE((gemm_mfma_kernel<WPB, NT, MT, CK, E>), lds_bytes);                                     \
-    gemm_mfma_kernel<WPB, NT, MT, CK, E><<<p.grid, WPB * 64, lds_bytes, st>>>(x, M, K, w, n_tiles, n_stages, P, \
-                                                                              ldp, part_stride, p.whole);      \
+    launch_timed(tag, gemm_mfma_kernel<WPB, NT, MT, CK, E>, p.grid, WPB * 64, lds_bytes, st, x, M, K, w, n_tiles, \
+                 n_stages, P, ldp, part_stride, p.whole, nullptr, nullptr);                                       \
   } else
   MDZ_GEMM_CASE(4, 1, 2, 128)
   MDZ_GEMM_CASE(4, 1, 1, 128)
@@ -430,7 +429,7 @@ bool gemm_mfma_swiglu_supported(int dtype, int M, int N, int K) {
 
 template <typename E>
 static int launch_gemm_mfma_swiglu_t(const void* X, const void* Wp, void* U, int M, int N, int K, hipStream_t st) {
-  ProfScope prof_(M <= 32 ? PROF_GEMM_W32 : PROF_GEMM_W64, st);
+  const int tag = M <= 32 ? PROF_GEMM_W32 : PROF_GEMM_W64;
   const int n_tiles = N / 32, n_stages = K / 128, bands = N / 128, kNumCU = num_cus();
   const int grid = bands < kNumCU ? bands : kNumCU;
   MDZ_REQUIRE((int64_t)bands * n_stages * grid < (int64_t)1 << 31 && (int64_t)M * N < (int64_t)1 << 31, MDZ_ESHAPE,
@@ -439,8 +438,8 @@ static int launch_gemm_mfma_swiglu_t(const void* X, const void* Wp, void* U, int
   {                                                                                                                  \
     constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 2 * MT * 32 * 33 * 4;                                   \
     MDZ_SET_LDS_ONCE((gemm_mfma_kernel<4, 1, MT, 128, E, true>), lds_bytes);                                         \
-    gemm_mfma_kernel<4, 1, MT, 128, E, true><<<grid, 256, lds_bytes, st>>>((const E*)X, M, K, (const E*)Wp, n_tiles, \
-                                                                           n_stages, nullptr, 0, 0, 1, (E*)U);       \
+    launch_timed(tag, gemm_mfma_kernel<4, 1, MT, 128, E, true>, grid, 256, lds_bytes, st, (const E*)X, M, K,         \
+                 (const E*)Wp, n_tiles, n_stages, nullptr, 0, 0, 1, (E*)U, nullptr);                                  \
   }
   if (M <= 32) MDZ_SWIGLU_CASE(1) else MDZ_SWIGLU_CASE(2)
 #undef MDZ_SWIGLU_CASE
@@ -458,13 +457,19 @@ int gemm_mfma_argmax_cands(int M, int N, int K) { return plan_gemm(M, N, K, 1).g
 template <typename E>
 static int launch_gemm_mfma_argmax_t(const void* X, const void* Wp, int M, int N, int K, ArgCand* cand, hipStream_t st) {
   const GemmPlan p = plan_gemm(M, N, K, 1);
-  ProfScope prof_(p.mt == 2 ? PROF_GEMM_W64 : PROF_GEMM_W32, st);
+  const int tag = p.mt == 2 ? PROF_GEMM_W64 : PROF_GEMM_W32;
   const int n_tiles = N / 32, n_stages = K / 128, bands = (n_tiles + 3) / 4;
   MDZ_REQUIRE(p.wpb == 4 && p.nt == 1 && p.ck == 128 && p.whole, MDZ_EUNSUPPORTED, "gemm: no argmax kernel for plan %d,%d,%d",
               p.wpb, p.nt, p.ck);
   MDZ_REQUIRE((int64_t)bands * n_stages * p.grid < (int64_t)1 << 31, MDZ_ESHAPE, "gemm: %d x %d units overflow", bands,
               n_stages);
-#define MDZ_ARGMAX_CASE(MT)                                                                                            {                                                                                                                       constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 4 * MT * 32 * 33 * 4;                                        MDZ_SET_LDS_ONCE((gemm_mfma_kernel<4, 1, MT, 128, E, false, true>), lds_bytes);                                       gemm_mfma_kernel<4, 1, MT, 128, E, false, true><<<p.grid, 256, lds_bytes, st>>>(                                          (const E*)X, M, K, (const E*)Wp, n_tiles, n_stages, nullptr, 0, 0, 1, nullptr, cand);                           }
+#define MDZ_ARGMAX_CASE(MT)                                                                                    \
+  {                                                                                                             \
+    constexpr int lds_bytes = 2 * MT * 32 * (128 * 2 + 16) + 4 * MT * 32 * 33 * 4;                              \
+    MDZ_SET_LDS_ONCE((gemm_mfma_kernel<4, 1, MT, 128, E, false, true>), lds_bytes);                             \
+    launch_timed(tag, gemm_mfma_kernel<4, 1, MT, 128, E, false, true>, p.grid, 256, lds_bytes, st, (const E*)X, \
+                 M, K, (const E*)Wp, n_tiles, n_stages, nullptr, 0, 0, 1, nullptr, cand);                       \
+  }
   if (p.mt == 1) MDZ_ARGMAX_CASE(1) else MDZ_ARGMAX_CASE(2)
 #undef MDZ_ARGMAX_CASE
   MDZ_LAUNCH_CHECK();

@@ -1,7 +1,11 @@
-// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch.
-// Off by default (a single predictable branch per launch).  medusa_profile_begin creates the event
-// pool, so no hot-path call ever creates an event.  Process-global: meant for a benchmark's own thread.
+// Optional per-kernel timing.  Two forms: ProfScope records HIP events on the caller's stream around whatever is
+// launched inside the scope (the event packets between kernels add 1-2 us per scope), and launch_timed launches
+// ONE kernel whose own start and end timestamps the dispatch records into an event pair (hipExtLaunchKernelGGL: no
+// packets between kernels, the duration a kernel trace shows).  Off by default (a single predictable branch per
+// launch).  medusa_profile_begin creates the event pool, so no hot-path call ever creates an event.
+// Process-global: meant for a benchmark's own thread.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 namespace mdz {
@@ -28,6 +32,19 @@ enum ProfTag {
 const char* prof_tag_name(int tag);
 bool prof_enabled();
 void prof_record(int tag, hipStream_t st, bool start);
+// hands out the next event pair of the pool for one kernel's own timestamps; false if the pool is full
+bool prof_kernel_events(int tag, hipEvent_t* start, hipEvent_t* stop);
+
+// kernel<<<grid, block, lds, st>>>(args...), timed by the dispatch itself while the profile is recording
+template <typename... KArgs, typename... Args>
+inline void launch_timed(int tag, void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds, hipStream_t st,
+                         Args... args) {
+  hipEvent_t e0, e1;
+  if (prof_enabled() && prof_kernel_events(tag, &e0, &e1))
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, st, e0, e1, 0, static_cast<KArgs>(args)...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, static_cast<KArgs>(args)...);
+}
 
 struct ProfScope {
   int tag;

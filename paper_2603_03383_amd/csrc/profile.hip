@@ -40,6 +40,18 @@ void prof_record(int tag, hipStream_t st, bool start) {
   }
 }
 
+bool prof_kernel_events(int tag, hipEvent_t* start, hipEvent_t* stop) {
+  if (g.n >= g.cap) {
+    ++g.dropped;
+    return false;
+  }
+  g.tags[g.n] = tag;
+  *start = g.ev[2 * g.n];
+  *stop = g.ev[2 * g.n + 1];
+  ++g.n;
+  return true;
+}
+
 }  // namespace mdz
 
 using namespace mdz;
