@@ -117,8 +117,8 @@ def timed(fn, warmup, steps):
 
 
 def profiled(fn, steps, launches_per_step):
-    """{family: {launches, total_us, ...}} over `steps` instrumented runs of fn (HIP events: the GEMM kernels' own start / end
-    timestamps, taken by the dispatch; event records on the stream around every other launch)."""
+    """{family: {launches, total_us, ...}} over `steps` instrumented runs of fn (HIP events: the GEMM, norm and attention
+    kernels' own start / end timestamps, taken by the dispatch; event records on the stream around the other calls)."""
     import torch
     import paper_2603_03383_amd as P
     P.medusa_profile_begin(steps * launches_per_step)
@@ -356,8 +356,8 @@ def main():
 
     ms = timed(one_step, args.warmup, args.steps)
 
-    # instrumented steps: HIP events on the launch stream (a GEMM launch's own start / end timestamps; records around
-    # the other launches)
+    # instrumented steps: HIP events on the launch stream (a GEMM, norm or attention launch's own start / end
+    # timestamps; records around the other calls)
     prof = profiled(one_step, args.steps, w.n_layers * 12 + 64)
 
     # the autoregressive baseline (Section 4.1): the same weights and prefix, the single-node tree, timed the same way

@@ -579,7 +579,6 @@ template <typename E, bool Q8, int NU>
 static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv, const float* cs, const KvGeom& g, void* kc,
                                    void* vc, int layer, const int32_t* seq_len, int B, int max_prefix, void* att_out,
                                    void* scratch, int64_t scratch_bytes, hipStream_t st) {
-  ProfScope prof_(PROF_ATTN, st);
   if (B == 0) return MDZ_OK;
   // the merge buffer [4][128][32 NU + 2] + [4][2][32 NU] floats overlays the staged Q tile
   constexpr int lds_bytes = 4 * kHD * (32 * NU + 2) * 4 + 4 * 2 * 32 * NU * 4;
@@ -593,11 +592,11 @@ static int launch_attention_mfma_t(int tree, const void* q, const Partials* qkv,
   float* part_ml = part_o + (int64_t)B * nq * splits * kTQ * kHD;
   dim3 grid(splits, nq, B * (3 - NU));  // NU = 1: blockIdx.z = 2 * sequence + half
   const Partials none = single_slot(nullptr, 0, 0);
-  attn_tree_mfma_kernel<E, Q8, NU><<<grid, 256, lds_bytes, st>>>(tree, (const E*)q, qkv ? *qkv : none, cs, g, (E*)kc, (E*)vc,
-                                                             layer, seq_len, max_prefix, (E*)att_out, part_o, part_ml);
+  launch_timed(PROF_ATTN, attn_tree_mfma_kernel<E, Q8, NU>, grid, 256, lds_bytes, st, tree, (const E*)q, qkv ? *qkv : none, cs, g,
+               (E*)kc, (E*)vc, layer, seq_len, max_prefix, (E*)att_out, part_o, part_ml);
   MDZ_LAUNCH_CHECK();
   if (splits > 1) {
-    attn_combine_kernel<E><<<dim3(nq, B, kTQ / 16), 256, 0, st>>>(nq, splits, part_o, part_ml, (E*)att_out);
+    launch_timed(PROF_ATTN, attn_combine_kernel<E>, dim3(nq, B, kTQ / 16), 256, 0, st, nq, splits, part_o, part_ml, (E*)att_out);
     MDZ_LAUNCH_CHECK();
   }
   return MDZ_OK;

@@ -167,27 +167,28 @@ __global__ void __launch_bounds__(1024) residual_rmsnorm_vec4_kernel(float* __re
 // feed-forward block takes binary16 operands.
 static int launch_norm_with_rope(int dtype, int out_dtype, float* x, const Partials& part, const void* g, void* xn,
                                  int rows, int d, float eps, RopeJob rope, hipStream_t st) {
-  ProfScope prof_(PROF_NORM, st);
   if (rows == 0) return MDZ_OK;
   const int entries = rope.n_blocks ? rope.B * host_tree(rope.tree)->T * rope.half : 0;
   if (out_dtype != dtype) {
     MDZ_REQUIRE(dtype == MDZ_BF16 && out_dtype == MDZ_FP16 && rope.n_blocks == 0, MDZ_EINVAL,
                 "norm: only bf16 gains with binary16 output may differ in type");
     if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0)
-      residual_rmsnorm_vec4_kernel<bf16_t, f16_t><<<rows, 1024, 0, st>>>(x, part, (const bf16_t*)g, (f16_t*)xn, d, eps, rows, rope);
+      launch_timed(PROF_NORM, residual_rmsnorm_vec4_kernel<bf16_t, f16_t>, rows, 1024, 0, st, x, part, (const bf16_t*)g, (f16_t*)xn, d,
+                   eps, rows, rope);
     else
-      residual_rmsnorm_kernel<bf16_t, f16_t><<<rows, 256, 0, st>>>(x, part, (const bf16_t*)g, (f16_t*)xn, d, eps, rows, rope);
+      launch_timed(PROF_NORM, residual_rmsnorm_kernel<bf16_t, f16_t>, rows, 256, 0, st, x, part, (const bf16_t*)g, (f16_t*)xn, d, eps,
+                   rows, rope);
     MDZ_LAUNCH_CHECK();
     return MDZ_OK;
   }
   if (d == 4096 && part.ld % 4 == 0 && part.stride % 4 == 0 && ((uintptr_t)g | (uintptr_t)xn) % 16 == 0) {
     rope.n_blocks = (entries + 1023) / 1024;
-    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_vec4_kernel<E><<<rows + rope.n_blocks, 1024, 0, st>>>(x, part, (const E*)g, (E*)xn, d,
-                                                                                              eps, rows, rope)));
+    MDZ_WITH_ELEM(dtype, (launch_timed(PROF_NORM, residual_rmsnorm_vec4_kernel<E>, rows + rope.n_blocks, 1024, 0, st, x, part,
+                                       (const E*)g, (E*)xn, d, eps, rows, rope)));
   } else {
     rope.n_blocks = (entries + 255) / 256;
-    MDZ_WITH_ELEM(dtype, (residual_rmsnorm_kernel<E><<<rows + rope.n_blocks, 256, 0, st>>>(x, part, (const E*)g, (E*)xn, d, eps,
-                                                                                        rows, rope)));
+    MDZ_WITH_ELEM(dtype, (launch_timed(PROF_NORM, residual_rmsnorm_kernel<E>, rows + rope.n_blocks, 256, 0, st, x, part,
+                                       (const E*)g, (E*)xn, d, eps, rows, rope)));
   }
   MDZ_LAUNCH_CHECK();
   return MDZ_OK;
