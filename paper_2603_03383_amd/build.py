@@ -49,6 +49,8 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
 
 
 PROBES = os.path.join(HERE, "probes")
+# the stamps probe compiles the library's own kernel sources with their per-workgroup time stamps switched on
+PROBE_FLAGS = {"stamps_probe.hip": ["-DMDZ_STAMPS", "-I", os.path.join(os.path.dirname(HERE), "include"), "-I", CSRC]}
 
 
 def build_probes(verbose: bool = True):
@@ -61,7 +63,7 @@ def build_probes(verbose: bool = True):
             continue
         exe = os.path.join(PROBES, f[:-4])
         cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", os.path.join(PROBES, f), "-o", exe]
+               "-packed-fp32-ops", *PROBE_FLAGS.get(f, []), os.path.join(PROBES, f), "-o", exe]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {f}:\n{r.stdout}\n{r.stderr}")

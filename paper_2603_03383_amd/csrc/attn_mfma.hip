@@ -113,6 +113,7 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
                           const int32_t* __restrict__ seq_len, int max_prefix, E* __restrict__ att_out,
                           float* __restrict__ part_o, float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
+  MDZ_STAMP(0);
   const TreeTables& t = c_trees[tree];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qi = lane & 31, gh = lane >> 5;
@@ -284,7 +285,9 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
       stage_q(lo[0], hi[0]);
     }
   }
+  MDZ_STAMP(1);
   __syncthreads();  // Q tile complete; the tree rows written above are complete (stores drain before a barrier)
+  MDZ_STAMP(2);
   // B operand of scores^T: lane holds query 32u + qi, features 16ks + 8gh .. +7
   const uint8_t* qfrag = q_lds + qi * kQRow + gh * 16;
   uint64_t mq[NU];
@@ -406,6 +409,7 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
     }
   }
 
+  MDZ_STAMP(3);
   // ---- merge the four waves through LDS (fixed order) ------------------------------------------
   __syncthreads();  // every wave is done reading the Q tile that the merge buffer overlays
   float* o_lds = lds;                             // [4][kHD][kOPadN]
@@ -479,6 +483,7 @@ __global__ void __launch_bounds__(256, NU == 1 ? 2 : 1)
       part_ml[(pidx * 2 + 1) * kTQ + q_out] = L;
     }
   }
+  MDZ_STAMP(4);
 }
 
 // Merges the key-splits of 16 queries of one (sequence, head): fixed order, exact same weighting rule as above.

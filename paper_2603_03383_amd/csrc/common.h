@@ -31,6 +31,20 @@ void set_error(const char* fmt, ...);
   } while (0)
 #define MDZ_LAUNCH_CHECK() MDZ_HIP(hipGetLastError())
 
+// Wall-clock stamps per workgroup, compiled in only by the timing probe (probes/stamps_probe.hip, -DMDZ_STAMPS):
+// stamp i of workgroup w (its linear index in the grid) goes to mdz_stamps[8 w + i], in units of 10 ns.  In the
+// library build the macro is empty.
+#ifdef MDZ_STAMPS
+__device__ unsigned long long mdz_stamps[8 * 4096];
+#define MDZ_STAMP(i)                                                                                             \
+  do {                                                                                                           \
+    if (threadIdx.x == 0)                                                                                        \
+      mdz_stamps[(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * 8 + (i)] = wall_clock64();  \
+  } while (0)
+#else
+#define MDZ_STAMP(i) ((void)0)
+#endif
+
 // ---- device facts --------------------------------------------------------------------------------
 // Compute units of the current device (read once; 256 when no device can be asked: host-only plan introspection).
 int num_cus();

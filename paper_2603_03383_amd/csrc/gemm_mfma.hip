@@ -68,6 +68,7 @@ __global__ void __launch_bounds__(WPB * 64)
       if (lane < ROWS && lane < M) cand[(int64_t)lane * (G * WPB) + w * WPB + wave] = ArgCand{best_v, best_i};
     }
   };
+  MDZ_STAMP(0);
   if (u_lo >= u_hi) {
     write_cand();
     return;
@@ -256,6 +257,7 @@ __global__ void __launch_bounds__(WPB * 64)
   __builtin_amdgcn_sched_barrier(0);
   store_x(0);
   __syncthreads();
+  MDZ_STAMP(1);
   // Steady state: two units (four half stages) per trip.  Before a half stage is multiplied the half stage
   // three ahead of it is requested, so three half stages of W per wave are in flight during the MFMAs;
   // sched_barrier pins that order.  The X columns of the next unit are requested at the start of a unit and
@@ -266,6 +268,7 @@ __global__ void __launch_bounds__(WPB * 64)
     __builtin_amdgcn_sched_barrier(0);
     compute(0, 0, wb[0]);
     __builtin_amdgcn_sched_barrier(0);
+    if (u == u_lo) MDZ_STAMP(2);
     load_w(wb[0]);
     __builtin_amdgcn_sched_barrier(0);
     compute(0, 1, wb[1]);
@@ -290,6 +293,7 @@ __global__ void __launch_bounds__(WPB * 64)
     store_x(0);
     __syncthreads();
   }
+  MDZ_STAMP(3);
   write_cand();
 }
 
