@@ -79,6 +79,8 @@ def test_argument_errors_are_status_codes():
     assert lib.accept_longest_prefix(0, None, None, 1, None, None, None, None, None, None, None) == -1
     assert lib.kv_compact(kv, 0, None, None, None, None, 1, 10, None) == -1
     assert b"NULL" in lib.medusa_last_error()
+    assert lib.medusa_pack_weight_bf16_as_f16(None, 32, 128, None, 32, 0, 1, None) == -1
+    assert lib.medusa_pack_weight(P.MDZ_BF16, None, 32, 128, None, 32, 0, 1, None) == -1
     assert P.medusa_packed_bytes(P.MDZ_BF16, 4096, 4096) == 4096 * 4096 * 2
     assert P.medusa_pack_tile_rows(P.MDZ_BF16) == 32 and P.medusa_pack_tile_rows(P.MDZ_FP32) == 16
     # fp16 shares the 16-bit layouts
