@@ -14,9 +14,11 @@ extern "C" {
 
 /* ---- per-kernel timing ------------------------------------------------------------------------------ */
 
-/* Starts recording a HIP-event pair on the caller's stream around every kernel launch the library makes,
- * for at most max_launches launches (further ones are counted as dropped).  Creates its events here, so
- * hot-path calls still allocate nothing.  Process-global; not thread-safe. */
+/* Starts recording one HIP-event pair per launch the library makes, for at most max_launches launches (further
+ * ones are counted as dropped).  The GEMM, norm and attention kernels are launched so that the dispatch itself
+ * writes the kernel's start and end timestamps into the pair (no packets between kernels: the duration a kernel
+ * trace shows); for the other calls the pair is recorded on the caller's stream around the call, which adds 1-2 us.
+ * Creates its events here, so hot-path calls still allocate nothing.  Process-global; not thread-safe. */
 int medusa_profile_begin(int max_launches);
 
 /* Stops recording, waits for the recorded events, and writes one text line per kernel family into the HOST
